@@ -1,0 +1,229 @@
+"""Pins for the oracle's whole-stage function: the invariants the method fixes.
+
+  I1  chunked prefill == unchunked prefill                          (bitwise)
+  I2  a decode row == the last row of a full causal prefill          (bitwise)
+  I3  permuting physical pages behind the page table changes nothing (bitwise)
+  I5  a sequence's rows do not depend on what else is in the batch   (bitwise)
+plus degenerate weights (zero projections), a dense unpaged textbook layer built from library
+matmuls, and the stored digest of the tiny configuration.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_14775_amd import synth
+from helpers import hidden_np, layer_weights_np, pool_np, small_shape
+
+SHAPE = small_shape(num_layers=2, hidden=64, n_q_heads=4, n_kv_heads=2, head_dim=16, intermediate=96)
+
+
+def run(shape, weights, seqs, bt, num_pages, kp, vp, hidden):
+    nt = [n for n, _ in seqs]
+    cl = [c for _, c in seqs]
+    return oracle.stage_forward(shape, weights, nt, cl, bt, num_pages, kp, vp, hidden)
+
+
+def fresh_pools(shape, num_pages, fill=0x7FC1):
+    n = shape.num_layers * synth.pool_elems_per_layer(shape, num_pages)
+    return np.full(n, fill, dtype=np.uint16), np.full(n, fill, dtype=np.uint16)
+
+
+@pytest.fixture(scope="module")
+def weights():
+    return layer_weights_np(SHAPE, seed=3)
+
+
+@pytest.mark.parametrize("split", [[64], [32, 32], [48, 16], [1, 62, 1], [17, 30, 17]])
+def test_I1_chunked_equals_unchunked_bitwise(weights, split):
+    total, num_pages = 64, 6
+    bt = np.array([[4, 1, 5, 0]], dtype=np.int32)
+    x = hidden_np(SHAPE, 5, total)
+    kp0, vp0 = fresh_pools(SHAPE, num_pages)
+    full, _ = run(SHAPE, weights, [(total, 0)], bt, num_pages, kp0, vp0, x)
+    kp, vp = fresh_pools(SHAPE, num_pages)
+    outs, done = [], 0
+    for n in split:
+        o, _ = run(SHAPE, weights, [(n, done)], bt, num_pages, kp, vp, x[done:done + n])
+        outs.append(o)
+        done += n
+    assert np.array_equal(np.concatenate(outs), full)
+    assert np.array_equal(kp, kp0) and np.array_equal(vp, vp0)
+
+
+def test_I2_decode_row_is_last_row_of_full_prefill(weights):
+    n, num_pages = 40, 4
+    bt = np.array([[2, 0, 3]], dtype=np.int32)
+    x = hidden_np(SHAPE, 6, n + 1)
+    kp0, vp0 = fresh_pools(SHAPE, num_pages)
+    full, _ = run(SHAPE, weights, [(n + 1, 0)], bt, num_pages, kp0, vp0, x)
+    kp, vp = fresh_pools(SHAPE, num_pages)
+    run(SHAPE, weights, [(n, 0)], bt, num_pages, kp, vp, x[:n])
+    dec, _ = run(SHAPE, weights, [(1, n)], bt, num_pages, kp, vp, x[n:])
+    assert np.array_equal(dec[0], full[n])
+    assert np.array_equal(kp, kp0) and np.array_equal(vp, vp0)
+
+
+def test_I3_physical_page_permutation_is_invisible():
+    shape = synth.SHAPES["tiny"]
+    w = layer_weights_np(shape, seed=0)
+    batch = synth.make_batch("tiny", seed=0)
+    x = hidden_np(shape, 0, batch.num_tokens)
+    kp, vp = pool_np(shape, 0, batch.num_blocks)
+    a, a16 = oracle.stage_forward(shape, w, batch.new_tokens, batch.cached_len, batch.block_tables,
+                                  batch.num_blocks, kp.copy(), vp.copy(), x)
+    rng = np.random.default_rng(99)
+    perm = rng.permutation(batch.num_blocks)             # new physical id of old page i
+    bt2 = np.where(batch.block_tables >= 0, perm[np.clip(batch.block_tables, 0, None)], -1).astype(np.int32)
+    per_page = shape.n_kv_heads * shape.page_size * shape.head_dim
+    kp2 = np.empty_like(kp); vp2 = np.empty_like(vp)
+    k_pages = kp.reshape(shape.num_layers, batch.num_blocks, per_page)
+    v_pages = vp.reshape(shape.num_layers, batch.num_blocks, per_page)
+    kp2.reshape(k_pages.shape)[:, perm, :] = k_pages
+    vp2.reshape(v_pages.shape)[:, perm, :] = v_pages
+    kq, vq = kp2.copy(), vp2.copy()
+    b, b16 = oracle.stage_forward(shape, w, batch.new_tokens, batch.cached_len, bt2, batch.num_blocks, kq, vq, x)
+    assert np.array_equal(a, b) and np.array_equal(a16, b16)
+
+
+def test_I5_rows_do_not_depend_on_batch_composition(weights):
+    num_pages = 12
+    seqs = [(20, 0), (1, 30), (7, 9), (1, 15)]
+    bt = np.array([[0, 1, -1], [2, 3, -1], [4, -1, -1], [5, -1, -1]], dtype=np.int32)
+    T = sum(n for n, _ in seqs)
+    x = hidden_np(SHAPE, 7, T)
+    kp, vp = pool_np(SHAPE, 7, num_pages)
+    full, _ = run(SHAPE, weights, seqs, bt, num_pages, kp.copy(), vp.copy(), x)
+    offs = np.concatenate([[0], np.cumsum([n for n, _ in seqs])])
+    # each sequence alone, and the batch in reverse order
+    for s in range(4):
+        o, _ = run(SHAPE, weights, [seqs[s]], bt[s:s + 1], num_pages, kp.copy(), vp.copy(), x[offs[s]:offs[s + 1]])
+        assert np.array_equal(o, full[offs[s]:offs[s + 1]])
+    order = [3, 2, 1, 0]
+    xr = np.concatenate([x[offs[s]:offs[s + 1]] for s in order])
+    o, _ = run(SHAPE, weights, [seqs[s] for s in order], bt[order], num_pages, kp.copy(), vp.copy(), xr)
+    got = {s: o[sum(seqs[r][0] for r in order[:i]):][:seqs[s][0]] for i, s in enumerate(order)}
+    for s in range(4):
+        assert np.array_equal(got[s], full[offs[s]:offs[s + 1]])
+
+
+def test_zero_output_projections_pass_input_through_bitwise(weights):
+    w = [dict(l) for l in weights]
+    for l in w:
+        l["wo"] = np.zeros_like(l["wo"]); l["wdown"] = np.zeros_like(l["wdown"])
+    x = hidden_np(SHAPE, 8, 21)
+    kp, vp = fresh_pools(SHAPE, 3)
+    out, out16 = run(SHAPE, w, [(21, 0)], np.array([[0, 1]], dtype=np.int32), 3, kp, vp, x)
+    assert np.array_equal(out16, x)
+    assert np.array_equal(out, oracle.bf16_to_f64(x))
+    assert (kp != 0x7FC1).sum() == SHAPE.num_layers * 21 * SHAPE.n_kv_heads * SHAPE.head_dim
+
+
+def test_zero_gate_removes_the_mlp_exactly(weights):
+    w0 = [dict(l) for l in weights]
+    w1 = [dict(l) for l in weights]
+    for l in w0:
+        l["wgate"] = np.zeros_like(l["wgate"])
+    for l in w1:
+        l["wdown"] = np.zeros_like(l["wdown"])
+    x = hidden_np(SHAPE, 9, 18)
+    bt = np.array([[1, 0]], dtype=np.int32)
+    a, _ = run(SHAPE, w0, [(18, 0)], bt, 2, *fresh_pools(SHAPE, 2), x)
+    b, _ = run(SHAPE, w1, [(18, 0)], bt, 2, *fresh_pools(SHAPE, 2), x)
+    assert np.array_equal(a, b)
+
+
+def test_has_qkv_bias_changes_output_and_zero_bias_does_not():
+    import dataclasses
+    shape_b = dataclasses.replace(SHAPE, has_qkv_bias=True)
+    wb = layer_weights_np(shape_b, seed=3)
+    x = hidden_np(SHAPE, 10, 12)
+    bt = np.array([[0]], dtype=np.int32)
+    with_bias, _ = run(shape_b, wb, [(12, 0)], bt, 1, *fresh_pools(SHAPE, 1), x)
+    wz = [dict(l) for l in wb]
+    for l in wz:
+        for n in ("bq", "bk", "bv"):
+            l[n] = np.zeros_like(l[n])
+    zero_bias, _ = run(shape_b, wz, [(12, 0)], bt, 1, *fresh_pools(SHAPE, 1), x)
+    no_bias, _ = run(SHAPE, [{k: v for k, v in l.items() if k[0] != "b"} for l in wb], [(12, 0)], bt, 1,
+                     *fresh_pools(SHAPE, 1), x)
+    assert np.array_equal(zero_bias, no_bias)
+    assert np.abs(with_bias - no_bias).max() > 1e-4
+
+
+# ------------------------------------------------------------------ dense textbook layer
+def _bf16_round(a):
+    return oracle.bf16_to_f64(oracle.f64_to_bf16(a))
+
+
+def _dense_layer(shape, w, x):
+    """One decoder layer on a single full sequence, unpaged, from dense library matmuls."""
+    f = {k: oracle.bf16_to_f64(v) for k, v in w.items()}
+    n, H = x.shape
+    d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
+    def norm(a, g):
+        return a / np.sqrt((a * a).mean(axis=1, keepdims=True) + shape.rms_eps) * g
+    def rot(a, heads):
+        a = a.reshape(n, heads, d)
+        j = np.arange(d // 2)
+        ang = np.arange(n)[:, None] * shape.rope_theta ** (-2.0 * j / d)[None, :]
+        c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+        lo, hi = a[..., : d // 2], a[..., d // 2:]
+        return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+    h = norm(x, f["norm1"])
+    q = rot(h @ f["wq"].T, nq)
+    k = _bf16_round(rot(h @ f["wk"].T, nkv))
+    v = _bf16_round((h @ f["wv"].T).reshape(n, nkv, d))
+    o = np.zeros((n, nq, d))
+    mask = np.tril(np.ones((n, n), dtype=bool))
+    for hq in range(nq):
+        S = q[:, hq] @ k[:, hq // (nq // nkv)].T / math.sqrt(d)
+        S = np.where(mask, S, -np.inf)
+        P = np.exp(S - S.max(axis=1, keepdims=True)); P /= P.sum(axis=1, keepdims=True)
+        o[:, hq] = P @ v[:, hq // (nq // nkv)]
+    x = x + o.reshape(n, nq * d) @ f["wo"].T
+    h2 = norm(x, f["norm2"])
+    gate, up = h2 @ f["wgate"].T, h2 @ f["wup"].T
+    return x + (gate / (1 + np.exp(-gate)) * up) @ f["wdown"].T
+
+
+def test_stage_matches_dense_unpaged_layers():
+    shape = small_shape(num_layers=2, hidden=48, n_q_heads=6, n_kv_heads=3, head_dim=8, intermediate=80)
+    w = layer_weights_np(shape, seed=21)
+    n = 45
+    x = hidden_np(shape, 21, n)
+    got, _ = run(shape, w, [(n, 0)], np.array([[2, 0, 1]], dtype=np.int32), 3, *fresh_pools(shape, 3), x)
+    ref = oracle.bf16_to_f64(x)
+    for l in range(2):
+        ref = _dense_layer(shape, w[l], ref)
+    # bf16 rounding of K/V may flip on ~1e-16 differences, hence not exact; far below any real slip
+    np.testing.assert_allclose(got, ref, rtol=0, atol=2e-3 * np.abs(ref).max())
+    assert np.abs(got - ref).mean() < 1e-5
+
+
+def test_malformed_batches_are_rejected(weights):
+    x = hidden_np(SHAPE, 1, 4)
+    bt = np.array([[0]], dtype=np.int32)
+    kp, vp = fresh_pools(SHAPE, 1)
+    with pytest.raises(ValueError):
+        run(SHAPE, weights, [(4, 0)], np.array([[1]], dtype=np.int32), 1, kp, vp, x)     # page out of range
+    with pytest.raises(ValueError):
+        run(SHAPE, weights, [(4, 14)], bt, 1, kp, vp, x)                                  # needs two pages
+
+
+# ------------------------------------------------------------------ stored digest of the tiny configuration
+def test_tiny_configuration_matches_stored_values():
+    """Regression pin: values written by tests/golden/make_tiny_golden.py (oracle only)."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "tiny_seed0.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    shape = synth.SHAPES["tiny"]
+    w = layer_weights_np(shape, seed=0)
+    batch = synth.make_batch("tiny", seed=0)
+    x = hidden_np(shape, 0, batch.num_tokens)
+    kp, vp = pool_np(shape, 0, batch.num_blocks)
+    out, _ = oracle.stage_forward(shape, w, batch.new_tokens, batch.cached_len, batch.block_tables,
+                                  batch.num_blocks, kp, vp, x)
+    for t, j, val in rows:
+        assert out[int(t), int(j)] == pytest.approx(float(val), rel=1e-9, abs=1e-12)
