@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage forward on one MI355X: stage tokens/s on a mixed prefill+decode batch.
+
+A step is one gllm_stage_forward over one batch: all layers of the stage, every kernel of the hot
+path, inputs (weights, KV pool, hidden states) already resident in HBM; only the batch descriptor
+(a few hundred KB of int32) crosses PCIe inside the call, as it does in serving.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llama3_8b_pp4] [--no-cpu-baseline]
+
+Prints ONE JSON line.  `roofline` describes the bf16 MFMA GEMM kernel (all four projections of a
+layer are launches of it), measured with HIP events on the launch stream in a second pass of the
+same steps; `roofline_decode_attention` gives the HBM figure of the decode attention kernel;
+`cpu_baseline` times the CPU oracle on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def prefill_attn_flops(shape, batch):
+    f = 0
+    for n, c in zip(batch.new_tokens, batch.cached_len):
+        n, c = int(n), int(c)
+        if n > 1:
+            f += 4 * shape.head_dim * shape.n_q_heads * (n * c + n * (n + 1) // 2)
+    return f
+
+
+def decode_kv_bytes(shape, batch):
+    keys = sum(int(c) + 1 for n, c in zip(batch.new_tokens, batch.cached_len) if int(n) == 1)
+    return keys * shape.kv_bytes_per_token_layer
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="llama3_8b_pp4")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--batch-index", type=int, default=0, help="batch of the 70B-shaped series")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile-pass", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (no sharding or collectives); "
+                         "use --gpus 1.\n")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2504_14775_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible; the stage has no CPU path.\n")
+        sys.exit(3)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    shape = synth.SHAPES[args.config]
+    batch = synth.make_batch(args.config, args.seed, args.batch_index)
+    T = batch.num_tokens
+
+    stage = binding.stage_for_batches(shape, [batch], device=dev)
+    host_weights = []          # kept only if the oracle will be timed
+    for l in range(shape.num_layers):
+        w = synth.make_layer_weights(shape, args.seed, l, device=dev)
+        stage.load_layer(l, w)
+        if not args.no_cpu_baseline:
+            host_weights.append({k: synth.bf16_bits(v) for k, v in w.items()})
+        torch.cuda.synchronize()
+        del w
+    k_pool, v_pool = synth.make_pool(shape, args.seed, batch.num_blocks, device=dev)
+    stage.bind_kv_pool(k_pool, v_pool, batch.num_blocks)
+    hidden = synth.make_hidden(shape, args.seed, T, device=dev)
+    out = torch.empty(T, shape.hidden, dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+
+    # sample for the CPU baseline, taken before the forward touches the pool
+    sample = None
+    if not args.no_cpu_baseline:
+        dec = [i for i in range(batch.num_seqs) if batch.new_tokens[i] == 1][:8]
+        pre = [i for i in range(batch.num_seqs) if batch.new_tokens[i] > 1][:1]
+        ids = pre + dec
+        nt = [min(int(batch.new_tokens[i]), 40) for i in pre] + [1] * len(dec)
+        sub, kp, vp, _ = synth.compact_subset(shape, batch, ids, nt, k_pool, v_pool)
+        rows = []
+        offs = batch.row_offsets
+        for i, n in zip(ids, nt):
+            rows += list(range(int(offs[i]), int(offs[i]) + n))
+        sample = (sub, kp, vp, synth.bf16_bits(hidden[rows]))
+
+    def step():
+        stage.forward(batch.new_tokens, batch.cached_len, batch.block_tables, hidden, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = T * args.steps / elapsed
+
+    # ---- per-kernel pass: HIP events on the launch stream around every kernel ----
+    L = shape.num_layers
+    gemm_flop_step = T * shape.gemm_flop_per_token_layer * L
+    roofline = None
+    extra = {}
+    if not args.no_profile_pass:
+        stage.set_profiling(True)
+        for _ in range(args.steps):
+            step()
+        prof = stage.read_profile(reset=True)
+        stage.set_profiling(False)
+        per_step = {k: v[0] / args.steps for k, v in prof.items()}
+        launches = {k: v[1] // args.steps for k, v in prof.items()}
+        gemm_classes = ["gemm_qkv", "gemm_o", "gemm_gate_up_swiglu", "gemm_down"]
+        gemm_ms = sum(per_step[c] for c in gemm_classes)
+        gemm_launches = sum(launches[c] for c in gemm_classes)
+        achieved = gemm_flop_step / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+        roofline = {"kernel": "gemm_bf16_kernel", "bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": None, "launches_per_step": gemm_launches,
+                    "avg_launch_ms": round(gemm_ms / max(gemm_launches, 1), 5),
+                    "flop_per_launch": gemm_flop_step / max(gemm_launches, 1)}
+        H, I = shape.hidden, shape.intermediate
+        per_class_flop = {"gemm_qkv": 2 * T * H * shape.n_qkv, "gemm_o": 2 * T * shape.q_dim * H,
+                          "gemm_gate_up_swiglu": 4 * T * H * I, "gemm_down": 2 * T * H * I}
+        extra["gemm_tflops_by_projection"] = {
+            c: round(per_class_flop[c] * L / (per_step[c] * 1e-3) / 1e12, 1) for c in gemm_classes if per_step[c] > 0}
+        kvb = decode_kv_bytes(shape, batch)
+        if per_step.get("attn_decode", 0) > 0:
+            gbs = kvb * L / (per_step["attn_decode"] * 1e-3) / 1e9
+            extra["roofline_decode_attention"] = {
+                "kernel": "decode_attention_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(per_step["attn_decode"] / L, 5), "bytes_per_launch": kvb}
+        pf = prefill_attn_flops(shape, batch)
+        if per_step.get("attn_prefill", 0) > 0:
+            tf = pf * L / (per_step["attn_prefill"] * 1e-3) / 1e12
+            extra["roofline_prefill_attention"] = {
+                "kernel": "prefill_attention_kernel", "bound": "mfma", "achieved": round(tf, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                "avg_launch_ms": round(per_step["attn_prefill"] / L, 5), "flop_per_launch": pf}
+        extra["kernel_ms_per_step"] = {k: round(v, 4) for k, v in per_step.items()}
+        extra["kernel_ms_sum"] = round(sum(per_step.values()), 4)
+
+    # ---- CPU oracle on a bounded sample of the same batch ----
+    cpu = None
+    if sample is not None:
+        import oracle
+        sub, kp, vp, xs = sample
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        oracle.stage_forward(shape, host_weights, sub.new_tokens, sub.cached_len, sub.block_tables,
+                             sub.num_blocks, kp, vp, xs)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(sub.num_tokens / dt, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+               "sample": f"{sub.num_tokens} token rows of the same batch ({int((sub.new_tokens > 1).sum())} prefill-chunk "
+                         f"prefix, {int((sub.new_tokens == 1).sum())} decode rows), all {L} layers, {dt:.1f} s"}
+
+    line = {
+        "metric": "stage tokens/sec on mixed prefill+decode batch",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.config, "layers": L, "tokens_per_batch": T,
+                   "prefill_tokens": int(batch.new_tokens[batch.new_tokens > 1].sum()),
+                   "decode_seqs": int((batch.new_tokens == 1).sum()),
+                   "mean_decode_context": float(np.mean(batch.cached_len[batch.new_tokens == 1])) if (batch.new_tokens == 1).any() else 0.0,
+                   "seed": args.seed, "parallelism": "single GPU"},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    line.update(extra)
+    print(json.dumps(line))
+    stage.destroy()
+
+
+if __name__ == "__main__":
+    main()

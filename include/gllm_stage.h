@@ -1,0 +1,174 @@
+/*
+ * gllm_stage.h -- C ABI of the MI355X (gfx950) stage-forward library.
+ *
+ * The library runs ONE pipeline stage's forward pass over a hybrid micro-batch of
+ * chunked-prefill and decode tokens, the computation that a pipeline-parallel serving
+ * runtime with Token Throttling (arxiv 2504.14775) schedules:
+ *   - a stage worker receives activations, runs its share of decoder layers, and hands
+ *     activations on (paper section 3.4, description of the workers);
+ *   - prefill and decode tokens are merged into a single batch (section 3.1); a prompt may
+ *     be prefilled in chunks that attend to the chunks already cached (section 2.2,
+ *     "Scheduling Policies");
+ *   - the KV cache is paged and every stage shares one set of page tables; pages for the
+ *     new tokens are assigned before the micro-batch runs (section 3.4; caption of the
+ *     prefill case-study figure in section 3.2), so this library never allocates KV pages:
+ *     it only writes K/V into the pages the caller's tables name;
+ *   - weights and activations are bf16 (section 4.1).
+ * The layer arithmetic is the public Llama/Qwen decoder layer: pre-norm RMSNorm, QKV
+ * projection (optional bias), rotate-half RoPE, grouped-query causal attention with scale
+ * 1/sqrt(head_dim), output projection + residual, RMSNorm, SwiGLU MLP + residual.
+ *
+ * General rules
+ *   - Every pointer is marked HOST or DEVICE.  Device pointers must belong to the HIP
+ *     device that was current when the stage was created.
+ *   - Every call returns a gllm_status (0 = success, negative = error).  After an error,
+ *     gllm_last_error() gives a message.  Errors found by validation are reported before
+ *     anything is enqueued, so a failed call has no side effects on device memory.
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = the null stream).
+ *     gllm_stage_forward only enqueues work; it does not synchronise.
+ *   - A stage object is not thread safe; use one per stream.
+ *   - There is no CPU fallback: without a usable HIP device create() fails.
+ */
+#ifndef GLLM_STAGE_H
+#define GLLM_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t gllm_status;
+enum {
+    GLLM_OK = 0,
+    GLLM_E_INVALID = -1,     /* null pointer, bad shape, new_tokens < 1, cached_len < 0, too many sequences */
+    GLLM_E_CAPACITY = -2,    /* more tokens / positions / pages per sequence than the stage was created for */
+    GLLM_E_BLOCK_RANGE = -3, /* a page id outside [0, num_blocks) */
+    GLLM_E_BLOCK_ALIAS = -4, /* two (sequence, logical page) pairs that receive new tokens share a physical page */
+    GLLM_E_STATE = -5,       /* weights, KV pool or workspace not bound yet */
+    GLLM_E_HIP = -6,         /* a HIP runtime call failed */
+    GLLM_E_UNSUPPORTED = -7  /* shape outside what the kernels implement */
+};
+
+typedef struct gllm_stage gllm_stage;
+
+/* Shape and limits of a stage.  Supported: page_size == 16; head_dim in {64, 128};
+ * n_q_heads a multiple of n_kv_heads with at most 16 query heads per KV head; hidden and
+ * n_q_heads*head_dim multiples of 64; intermediate a multiple of 8. */
+typedef struct {
+    int32_t num_layers;
+    int32_t hidden;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t intermediate;
+    int32_t page_size;
+    int32_t has_qkv_bias;
+    int32_t max_tokens;          /* most new tokens in one batch */
+    int32_t max_seqs;            /* most sequences in one batch */
+    int32_t max_blocks_per_seq;  /* most pages one sequence may own */
+    int32_t max_position;        /* largest cached_len + new_tokens of any sequence */
+    double rms_eps;
+    double rope_theta;
+} gllm_stage_config;
+
+/* One layer's parameters.  DEVICE pointers, bf16, row-major [out_features][in_features]:
+ *   wq [n_q*d][hidden]  wk, wv [n_kv*d][hidden]  wo [hidden][n_q*d]
+ *   wgate, wup [intermediate][hidden]  wdown [hidden][intermediate]
+ *   norm1, norm2 [hidden] (RMSNorm gains before attention / before the MLP)
+ *   bq [n_q*d], bk, bv [n_kv*d]: required iff has_qkv_bias, else ignored (may be NULL). */
+typedef struct {
+    const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *norm1, *norm2, *bq, *bk, *bv;
+} gllm_layer_weights;
+
+/* A micro-batch (HOST memory, read completely before gllm_stage_forward returns).
+ * Sequence s contributes new_tokens[s] >= 1 rows at positions cached_len[s] ..
+ * cached_len[s]+new_tokens[s]-1; row i of it attends to positions 0 .. cached_len[s]+i.
+ * A decode step is new_tokens == 1.  Rows are packed in sequence order: the first row of
+ * sequence s is row sum_{r<s} new_tokens[r].  block_tables[s*block_table_stride + b] is
+ * the physical page holding positions 16b .. 16b+15 of sequence s; entries are read for
+ * b < ceil((cached_len+new_tokens)/16) only. */
+typedef struct {
+    int32_t num_seqs;
+    int32_t block_table_stride;
+    const int32_t* new_tokens;
+    const int32_t* cached_len;
+    const int32_t* block_tables;
+} gllm_batch;
+
+/* Creates a stage on the current HIP device: allocates the library-owned copies of the
+ * weights (filled by gllm_stage_load_layer), the RoPE table and the metadata staging. */
+gllm_status gllm_stage_create(const gllm_stage_config* cfg /*HOST*/, gllm_stage** out /*HOST*/);
+void gllm_stage_destroy(gllm_stage* stage);
+
+/* Message of the last failed call on this stage (or of the last failed create when stage
+ * is NULL).  The string is owned by the library and valid until the next call. */
+const char* gllm_last_error(const gllm_stage* stage);
+const char* gllm_status_name(gllm_status s);
+
+/* Activation workspace: the caller allocates workspace_bytes() of device memory (256-byte
+ * aligned) and binds it; the library never frees it.  Contents need not survive between
+ * forward calls. */
+size_t gllm_stage_workspace_bytes(const gllm_stage* stage);
+gllm_status gllm_stage_bind_workspace(gllm_stage* stage, void* workspace /*DEVICE*/, size_t bytes);
+
+/* Copies and repacks one layer's parameters into library-owned device buffers (QKV rows
+ * concatenated, gate/up rows interleaved in groups of 32, rows and columns padded to tile
+ * multiples).  The copy is enqueued on `stream`; the caller's tensors may be released once
+ * the stream has passed this point. */
+gllm_status gllm_stage_load_layer(gllm_stage* stage, int32_t layer, const gllm_layer_weights* w /*HOST struct of DEVICE ptrs*/,
+                                  void* stream);
+
+/* Binds the caller-owned paged KV pool (DEVICE, bf16), page_size = 16 slots per page:
+ *   k_pool [num_layers][num_blocks][n_kv][head_dim/8][16][8]
+ *   v_pool [num_layers][num_blocks][n_kv][head_dim][16]
+ * i.e. K keeps each 8-element group of a head vector contiguous per slot, V keeps the 16
+ * slots of one head-dimension contiguous.  The forward pass writes the K/V of the new
+ * tokens (K after RoPE), rounded to bf16 (nearest even), to
+ *   page = block_tables[s][pos / 16], slot = pos % 16
+ * of every layer, and reads all earlier positions from the pool. */
+gllm_status gllm_stage_bind_kv_pool(gllm_stage* stage, void* k_pool /*DEVICE*/, void* v_pool /*DEVICE*/,
+                                    int64_t num_blocks);
+
+/* Debug option: when nonzero, forward() also rejects batches in which two different
+ * (sequence, logical page) pairs that receive new tokens name the same physical page. */
+gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);
+
+/* Runs all layers of the stage on the batch.
+ *   hidden_in       DEVICE bf16 [T][hidden]   (T = sum of new_tokens)
+ *   hidden_out      DEVICE bf16 [T][hidden]   residual stream after the last layer, RNE to bf16
+ *   hidden_out_f32  DEVICE float [T][hidden] or NULL: the fp32 residual stream before that rounding
+ * The residual stream is kept in fp32 across the layers; GEMM and attention operands are bf16
+ * with fp32 accumulation.  Enqueues on `stream` and returns. */
+gllm_status gllm_stage_forward(gllm_stage* stage, const gllm_batch* batch /*HOST*/, const void* hidden_in,
+                               void* hidden_out, float* hidden_out_f32, void* stream);
+
+/* Per-kernel timing.  With profiling on, forward() brackets every kernel with HIP events on
+ * the caller's stream; gllm_stage_read_profile() synchronises those events and adds their
+ * durations to per-class totals.  Classes are listed by gllm_profile_class_name(i) for
+ * i in [0, gllm_profile_num_classes()).  ms and launches are HOST arrays of that length. */
+gllm_status gllm_stage_set_profiling(gllm_stage* stage, int32_t on);
+gllm_status gllm_stage_read_profile(gllm_stage* stage, double* ms /*HOST*/, int64_t* launches /*HOST*/, int32_t reset);
+int32_t gllm_profile_num_classes(void);
+const char* gllm_profile_class_name(int32_t i);
+
+/* ---- single operations on DEVICE buffers (the kernels the stage is built from), exported so
+ * that each can be tested and timed on its own.  All enqueue on `stream` and return. ---- */
+
+/* out[m][n] (op)= sum_k a[m][k] * w[n][k];  a: bf16 [m_rows][lda] with lda >= k, w: bf16 [n][ldw].
+ * Requirements: k a multiple of 64 and n a multiple of 128 (the stage pads its operands);
+ * a must be readable for round_up(m,128) rows.  mode: 0 store fp32 to out[m][ldc];
+ * 1 add into fp32 out[m][ldc]; 2 SwiGLU: columns come in groups of 64 = 32 gate + 32 up
+ * outputs, out is bf16 [m][ldc] with n/2 columns, out = silu(gate) * up. */
+gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
+                              int32_t m, int32_t n, int32_t k, int32_t mode, void* stream);
+
+/* h[t][j] = bf16(x[t][j] * rsqrt(mean_j x^2 + eps) * gamma[j]); x fp32 [rows][hidden]. */
+gllm_status gllm_op_rmsnorm(const float* x, const void* gamma_bf16, void* h_bf16, int32_t rows, int32_t hidden,
+                            double eps, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLLM_STAGE_H */

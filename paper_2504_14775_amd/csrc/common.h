@@ -1,0 +1,105 @@
+// Internal declarations shared by the HIP translation units of libgllm_stage (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPage = 16;        // KV slots per page
+constexpr int kWave = 64;        // lanes per wavefront
+
+// GEMM tile constants that the weight packer and the activation buffers must agree on.
+constexpr int kGemmPadM = 256;   // activation rows are readable up to a multiple of this
+constexpr int kGemmPadN = 256;   // packed weight rows are padded to a multiple of this
+constexpr int kGemmPadK = 64;    // packed weight columns / activation row strides are multiples of this
+constexpr int kSwigluGroup = 32; // gate/up interleave granularity of the packed gate-up matrix
+
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
+
+// ---- launchers (each enqueues on `stream` and returns the launch status) ----------------
+
+// out (op)= a[m x k] * w[n x k]^T, see gllm_op_gemm_bf16 in the public header.
+hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,
+                            int m, int n, int k, int mode, hipStream_t stream);
+
+// Residual stream entry: x = float(in_bf16), h = bf16(rmsnorm(x) * gamma).
+hipError_t launch_rmsnorm_from_bf16(const bf16_t* in, float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh,
+                                    int rows, int hidden, float eps, hipStream_t stream);
+// h = bf16(rmsnorm(x) * gamma) from the fp32 residual stream.
+hipError_t launch_rmsnorm(const float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh, int rows, int hidden,
+                          float eps, hipStream_t stream);
+// out_bf16 = RNE(x), and optionally a copy of x.
+hipError_t launch_cast_out(const float* x, bf16_t* out, float* out_f32, int64_t count, hipStream_t stream);
+
+// Weight repacking (device to device).
+hipError_t launch_copy_rows_padded(const bf16_t* src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_row0,
+                                   hipStream_t stream);
+hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, int hidden, bf16_t* dst,
+                               int64_t ld_dst, hipStream_t stream);
+
+struct RopeKvArgs {
+    const float* qkv;        // [T][ld_qkv] fp32: q heads, then k heads, then v heads
+    int64_t ld_qkv;
+    const bf16_t* bias;      // [n_qkv] or null
+    const float* rope_cs;    // [max_position][d/2][2] (cos, sin)
+    const int32_t* tok_pos;  // [T]
+    const int32_t* tok_page; // [T] physical page of the token's own position
+    bf16_t* q_out;           // [T][n_q*d] bf16, rotated
+    int64_t ld_q;
+    bf16_t* k_pool;          // this layer's K pool
+    bf16_t* v_pool;          // this layer's V pool
+    int T, n_q, n_kv, d;
+};
+hipError_t launch_rope_kv_write(const RopeKvArgs& a, hipStream_t stream);
+
+struct AttnArgs {
+    const bf16_t* q;          // [T][ld_q] rotated queries
+    int64_t ld_q;
+    const bf16_t* k_pool;     // this layer
+    const bf16_t* v_pool;
+    const int32_t* bt_flat;   // page ids, all sequences back to back
+    bf16_t* out;              // [T][ld_o] bf16 attention output
+    int64_t ld_o;
+    int n_q, n_kv, d;
+    float scale_log2;         // log2(e) / sqrt(d)
+};
+
+// Decode rows (one new token per sequence).  Work items split the keys of a row into
+// partitions; every item writes one partial per KV head, then a second kernel merges.
+struct DecodeItem {
+    int32_t row;       // token row
+    int32_t bt_off;    // offset of the sequence's first page id in bt_flat
+    int32_t kv_begin;  // first key of this partition (multiple of 32)
+    int32_t kv_end;    // one past the last key of this partition
+};
+struct DecodeRow {
+    int32_t row;        // token row
+    int32_t first_item; // first partial of this row
+    int32_t num_items;
+    int32_t pad;
+};
+hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
+                                   float* part_ml, hipStream_t stream);
+hipError_t launch_decode_combine(const AttnArgs& a, const DecodeRow* rows, int num_rows, const float* part_o,
+                                 const float* part_ml, hipStream_t stream);
+
+// Prefill chunks: one work item per 64 consecutive query rows of a chunk.
+struct PrefillItem {
+    int32_t row0;      // first token row of the tile
+    int32_t n_rows;    // valid query rows in the tile (1..64)
+    int32_t pos0;      // position of the first query row
+    int32_t bt_off;    // offset of the sequence's first page id in bt_flat
+};
+hipError_t launch_prefill_attention(const AttnArgs& a, const PrefillItem* items, int num_items, hipStream_t stream);

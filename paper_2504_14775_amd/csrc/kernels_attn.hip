@@ -1,0 +1,358 @@
+// Ragged paged attention for decode rows and prefill chunks on the CDNA4 matrix cores.
+//
+// Both kernels run the same inner step on a block of 32 keys (two pages) and one or more groups
+// of 16 "columns" (for a decode row: the query heads that share a KV head; for a prefill chunk:
+// 16 consecutive query rows of one head), in transposed form so that nothing has to be moved
+// between lanes:
+//     S^T[key][col]  = K[key][:] . Q[col][:]          two 16x16x32 MFMA chains (one per page)
+//     O^T[dim][col] += V^T[dim][key] . P^T[key][col]  one 16x16x32 MFMA per 16 dims
+// A 16x16x32 MFMA takes, per lane (r = lane % 16, G = lane / 16), 8 consecutive k-values of row r
+// (A operand) or column r (B operand), k-slots 8G..8G+7, and returns for column r the rows
+// 4G..4G+3.  So after the two S^T tiles a lane holds, for its column, keys 4G..4G+3 of page 0 and
+// of page 1 -- exactly the 8 k-slots it must supply as the B operand of the P.V product when those
+// 8 keys are assigned to k-slots 8G..8G+7.  The pool layouts make the matching A operands plain
+// coalesced loads:
+//   K page [d/8][16 slots][8]: k-step s of S^T reads the 1 KiB at (64 s + lane) * 16 bytes;
+//   V page [d][16 slots]:      dims 16b..16b+15 of P.V read 8 bytes at ((16b + r) * 16 + 4G) * 2.
+// Softmax is the running-maximum form in base 2 (scores are pre-multiplied by log2(e)/sqrt(d));
+// all reductions follow logical key order, so the result does not depend on which physical pages
+// hold the keys.
+#include "common.h"
+
+namespace {
+
+constexpr float kNegBig = -1.0e30f;
+
+template <int D>
+struct KvFrag {
+    u32x4 k[2][D / 32];  // [page][k-step]
+    u32x2 v[2][D / 16];  // [page][16-dim block]
+};
+
+template <int D>
+__device__ __forceinline__ void load_kv(KvFrag<D>& f, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+                                        int64_t page0, int64_t page1, int n_kv, int kvh, int lane) {
+    constexpr int64_t PH = (int64_t)D * kPage;  // elements of one (page, head)
+    const int r = lane & 15, G = lane >> 4;
+    const int64_t pg[2] = {page0, page1};
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const bf16_t* kb = kp + (pg[p] * n_kv + kvh) * PH + lane * 8;
+        const bf16_t* vb = vp + (pg[p] * n_kv + kvh) * PH + r * kPage + G * 4;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) f.k[p][s] = *reinterpret_cast<const u32x4*>(kb + s * 512);
+#pragma unroll
+        for (int b = 0; b < D / 16; ++b) f.v[p][b] = *reinterpret_cast<const u32x2*>(vb + b * 256);
+    }
+}
+
+// State of NB column groups across the key loop.
+template <int D, int NB>
+struct AttnState {
+    f32x4 o[NB][D / 16];
+    float m[NB];
+    float l[NB];
+};
+
+// One block of 32 keys starting at key index tb.
+//   limit[c]   : last key visible to this lane's column in group c (causal / partition limit)
+//   valid_end  : keys >= valid_end hold no data yet (their V bits are forced to zero)
+template <int D, int NB>
+__device__ __forceinline__ void attend_block(AttnState<D, NB>& st, KvFrag<D>& f, const bf16x8 (&qf)[NB][D / 32],
+                                             int tb, const int (&limit)[NB], int min_limit, int valid_end,
+                                             float scale_log2, int lane) {
+    const int G = lane >> 4;
+    if (tb + 32 > valid_end) {  // wave-uniform
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            int nv = valid_end - (tb + p * 16 + G * 4);
+            nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+            uint32_t m0 = nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0x0000FFFFu : 0u);
+            uint32_t m1 = nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0x0000FFFFu : 0u);
+#pragma unroll
+            for (int b = 0; b < D / 16; ++b) {
+                f.v[p][b][0] &= m0;
+                f.v[p][b][1] &= m1;
+            }
+        }
+    }
+    const bool need_mask = tb + 31 > min_limit;  // wave-uniform
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.k[0][s]), qf[c][s], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.k[1][s]), qf[c][s], s1, 0, 0, 0);
+        }
+        float sc[8];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            sc[v] = s0[v] * scale_log2;
+            sc[4 + v] = s1[v] * scale_log2;
+        }
+        if (need_mask) {
+            const int t0 = tb + G * 4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (t0 + v > limit[c]) sc[v] = kNegBig;
+                if (t0 + 16 + v > limit[c]) sc[4 + v] = kNegBig;
+            }
+        }
+        float bm = sc[0];
+#pragma unroll
+        for (int v = 1; v < 8; ++v) bm = fmaxf(bm, sc[v]);
+        bm = fmaxf(bm, __shfl_xor(bm, 16));
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        const float m_new = fmaxf(st.m[c], bm);
+        const float alpha = __builtin_amdgcn_exp2f(st.m[c] - m_new);
+        st.m[c] = m_new;
+        f32x8 p;
+        float psum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            p[v] = __builtin_amdgcn_exp2f(sc[v] - m_new);
+            psum += p[v];
+        }
+        st.l[c] = st.l[c] * alpha + psum;
+        const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+        for (int b = 0; b < D / 16; ++b) {
+            f32x4 o = st.o[c][b];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] *= alpha;
+            u32x4 vv = {f.v[0][b][0], f.v[0][b][1], f.v[1][b][0], f.v[1][b][1]};
+            st.o[c][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, o, 0, 0, 0);
+        }
+    }
+}
+
+// Walks key blocks [blk_begin, blk_end) (units of 32 keys) of one sequence.  Page ids are fetched 64
+// at a time, one per lane, and handed out with readlane.  last_page is the last page index of the
+// sequence that may be read (page ids past it are never dereferenced).
+template <int D, int NB>
+__device__ __forceinline__ void attend_range(AttnState<D, NB>& st, const bf16x8 (&qf)[NB][D / 32],
+                                             const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+                                             const int32_t* __restrict__ bt, int blk_begin, int blk_end,
+                                             int last_page, const int (&limit)[NB], int min_limit, int valid_end,
+                                             int n_kv, int kvh, float scale_log2, int lane) {
+    if (blk_begin >= blk_end) return;
+    int ids_base = blk_begin * 2;  // page index held by lane 0
+    int ids = bt[min(ids_base + lane, last_page)];
+    auto page_of = [&](int pi) -> int64_t {  // pi wave-uniform, within [ids_base, ids_base + 64)
+        return (int64_t)__builtin_amdgcn_readlane(ids, pi - ids_base);
+    };
+    auto load_block = [&](KvFrag<D>& f, int blk) {
+        int p0 = min(blk * 2, last_page), p1 = min(blk * 2 + 1, last_page);
+        load_kv<D>(f, kp, vp, page_of(p0), page_of(p1), n_kv, kvh, lane);
+    };
+    KvFrag<D> fa, fb;
+    load_block(fa, blk_begin);
+    for (int blk = blk_begin; blk < blk_end; blk += 2) {
+        // blocks blk and blk+1 use pages 2blk .. 2blk+3; refill the id window when it runs out
+        const bool has_b = blk + 1 < blk_end;
+        if (has_b) load_block(fb, blk + 1);
+        attend_block<D, NB>(st, fa, qf, blk * 32, limit, min_limit, valid_end, scale_log2, lane);
+        if (blk + 2 < blk_end) {
+            if ((blk + 2) * 2 + 3 >= ids_base + 64) {
+                ids_base = (blk + 2) * 2;
+                ids = bt[min(ids_base + lane, last_page)];
+            }
+            load_block(fa, blk + 2);
+        }
+        if (has_b) attend_block<D, NB>(st, fb, qf, (blk + 1) * 32, limit, min_limit, valid_end, scale_log2, lane);
+    }
+}
+
+template <int D, int NB>
+__device__ __forceinline__ void init_state(AttnState<D, NB>& st) {
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        st.m[c] = kNegBig;
+        st.l[c] = 0.f;
+#pragma unroll
+        for (int b = 0; b < D / 16; ++b) st.o[c][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Decode: grid (items, kv heads), 4 waves.  The item's key partition is cut into four runs of
+// 32-key blocks, one per wave; the waves' partial results are merged through LDS and written as
+// one partial (running max, sum, unnormalised output) per query head of the KV head.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
+                                                                float* __restrict__ part_o,
+                                                                float* __restrict__ part_ml) {
+    __shared__ float lds_o[4][16][D + 4];
+    __shared__ float lds_m[4][16], lds_l[4][16];
+    const DecodeItem it = items[blockIdx.x];
+    const int kvh = blockIdx.y;
+    const int g = a.n_q / a.n_kv;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15, G = lane >> 4;
+
+    bf16x8 qf[1][D / 32];
+    {
+        const bf16_t* qrow = a.q + (int64_t)it.row * a.ld_q + (int64_t)(kvh * g + r) * D;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (r < g) z = *reinterpret_cast<const u32x4*>(qrow + (s * 4 + G) * 8);
+            qf[0][s] = __builtin_bit_cast(bf16x8, z);
+        }
+    }
+    const int blk0 = it.kv_begin / 32;
+    const int nblk = (it.kv_end - it.kv_begin + 31) / 32;
+    const int per_wave = (nblk + 3) / 4;
+    const int b_begin = blk0 + min(wave * per_wave, nblk);
+    const int b_end = blk0 + min((wave + 1) * per_wave, nblk);
+    const int limit[1] = {it.kv_end - 1};
+    AttnState<D, 1> st;
+    init_state<D, 1>(st);
+    attend_range<D, 1>(st, qf, a.k_pool, a.v_pool, a.bt_flat + it.bt_off, b_begin, b_end, (it.kv_end - 1) / kPage,
+                       limit, it.kv_end - 1, it.kv_end, a.n_kv, kvh, a.scale_log2, lane);
+    float l = st.l[0];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (G == 0) {
+        lds_m[wave][r] = st.m[0];
+        lds_l[wave][r] = l;
+    }
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b)
+        *reinterpret_cast<f32x4*>(&lds_o[wave][r][b * 16 + G * 4]) = st.o[0][b];
+    __syncthreads();
+    // merge: thread -> (head j, 4-dim group)
+    for (int idx = threadIdx.x; idx < g * (D / 4); idx += 256) {
+        const int j = idx / (D / 4), e = (idx % (D / 4)) * 4;
+        float mw[4], ms = kNegBig;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            mw[w] = lds_m[w][j];
+            ms = fmaxf(ms, mw[w]);
+        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float ls = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float sc = __builtin_amdgcn_exp2f(mw[w] - ms);
+            const f32x4 ov = *reinterpret_cast<const f32x4*>(&lds_o[w][j][e]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] += ov[v] * sc;
+            ls += lds_l[w][j] * sc;
+        }
+        const int64_t slot = ((int64_t)blockIdx.x * a.n_q + kvh * g + j);
+        *reinterpret_cast<f32x4*>(part_o + slot * D + e) = acc;
+        if (e == 0) {
+            part_ml[slot * 2] = ms;
+            part_ml[slot * 2 + 1] = ls;
+        }
+    }
+}
+
+// grid (rows, query heads), D/4 threads: merges the partials of a row in partition order.
+template <int D>
+__global__ void decode_combine_kernel(AttnArgs a, const DecodeRow* __restrict__ rows, const float* __restrict__ part_o,
+                                      const float* __restrict__ part_ml) {
+    const DecodeRow rw = rows[blockIdx.x];
+    const int hq = blockIdx.y, e = threadIdx.x * 4;
+    float ms = kNegBig;
+    for (int i = 0; i < rw.num_items; ++i)
+        ms = fmaxf(ms, part_ml[((int64_t)(rw.first_item + i) * a.n_q + hq) * 2]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float ls = 0.f;
+    for (int i = 0; i < rw.num_items; ++i) {
+        const int64_t slot = (int64_t)(rw.first_item + i) * a.n_q + hq;
+        const float sc = __builtin_amdgcn_exp2f(part_ml[slot * 2] - ms);
+        const f32x4 ov = *reinterpret_cast<const f32x4*>(part_o + slot * D + e);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] += ov[v] * sc;
+        ls += part_ml[slot * 2 + 1] * sc;
+    }
+    const float inv = 1.0f / ls;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] *= inv;
+    *reinterpret_cast<bf16x4*>(a.out + (int64_t)rw.row * a.ld_o + hq * D + e) = __builtin_convertvector(acc, bf16x4);
+}
+
+// ------------------------------------------------------------------------------------------
+// Prefill: grid (items, query heads), one wave per workgroup.  An item is up to 16*NB consecutive
+// query rows of a chunk; the wave walks keys 0 .. position of its last valid row.
+// ------------------------------------------------------------------------------------------
+template <int D, int NB>
+__global__ __launch_bounds__(64) void prefill_attention_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
+    const PrefillItem it = items[blockIdx.x];
+    const int hq = blockIdx.y;
+    const int g = a.n_q / a.n_kv;
+    const int kvh = hq / g;
+    const int lane = threadIdx.x;
+    const int r = lane & 15, G = lane >> 4;
+
+    bf16x8 qf[NB][D / 32];
+    int limit[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        const int qi = min(c * 16 + r, it.n_rows - 1);  // rows past the tile repeat its last row (never stored)
+        limit[c] = it.pos0 + qi;
+        const bf16_t* qrow = a.q + (int64_t)(it.row0 + qi) * a.ld_q + (int64_t)hq * D;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+            qf[c][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + (s * 4 + G) * 8));
+    }
+    const int last_pos = it.pos0 + it.n_rows - 1;
+    AttnState<D, NB> st;
+    init_state<D, NB>(st);
+    attend_range<D, NB>(st, qf, a.k_pool, a.v_pool, a.bt_flat + it.bt_off, 0, last_pos / 32 + 1, last_pos / kPage,
+                        limit, it.pos0, last_pos + 1, a.n_kv, kvh, a.scale_log2, lane);
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        float l = st.l[c];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const float inv = 1.0f / l;
+        const int qi = c * 16 + r;
+        if (qi < it.n_rows) {
+            bf16_t* orow = a.out + (int64_t)(it.row0 + qi) * a.ld_o + (int64_t)hq * D;
+#pragma unroll
+            for (int b = 0; b < D / 16; ++b) {
+                f32x4 o = st.o[c][b];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) o[v] *= inv;
+                *reinterpret_cast<bf16x4*>(orow + b * 16 + G * 4) = __builtin_convertvector(o, bf16x4);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
+                                   float* part_ml, hipStream_t stream) {
+    if (num_items <= 0) return hipSuccess;
+    dim3 grid(num_items, a.n_kv);
+    if (a.d == 128) decode_attention_kernel<128><<<grid, 256, 0, stream>>>(a, items, part_o, part_ml);
+    else if (a.d == 64) decode_attention_kernel<64><<<grid, 256, 0, stream>>>(a, items, part_o, part_ml);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_combine(const AttnArgs& a, const DecodeRow* rows, int num_rows, const float* part_o,
+                                 const float* part_ml, hipStream_t stream) {
+    if (num_rows <= 0) return hipSuccess;
+    dim3 grid(num_rows, a.n_q);
+    if (a.d == 128) decode_combine_kernel<128><<<grid, 32, 0, stream>>>(a, rows, part_o, part_ml);
+    else if (a.d == 64) decode_combine_kernel<64><<<grid, 16, 0, stream>>>(a, rows, part_o, part_ml);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_attention(const AttnArgs& a, const PrefillItem* items, int num_items, hipStream_t stream) {
+    if (num_items <= 0) return hipSuccess;
+    dim3 grid(num_items, a.n_q);
+    if (a.d == 128) prefill_attention_kernel<128, 4><<<grid, 64, 0, stream>>>(a, items);
+    else if (a.d == 64) prefill_attention_kernel<64, 4><<<grid, 64, 0, stream>>>(a, items);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}

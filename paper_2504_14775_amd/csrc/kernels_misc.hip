@@ -1,0 +1,193 @@
+// Memory-bound helper kernels of the stage: RMSNorm, residual-stream entry/exit casts,
+// RoPE + paged KV write, weight repacking.  All are bound by HBM traffic and tiny next to
+// the GEMMs and the attention kernels.
+#include "common.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Sum over the 256 threads of a workgroup; every thread receives the total.
+__device__ __forceinline__ float block_sum_256(float v, float* red /*[4]*/) {
+    v = wave_sum(v);
+    int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = red[0] + red[1] + red[2] + red[3];
+    __syncthreads();
+    return t;
+}
+
+// One workgroup per row.  FROM_BF16: the row comes from the bf16 stage input and is also
+// written out as the fp32 residual stream.
+template <bool FROM_BF16>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t* __restrict__ in, float* __restrict__ x,
+                                                       const bf16_t* __restrict__ gamma, bf16_t* __restrict__ h,
+                                                       int64_t ldh, int hidden, float eps) {
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    float* xr = x + row * hidden;
+    const bf16_t* ir = FROM_BF16 ? in + row * hidden : nullptr;
+    float ss = 0.f;
+    for (int j = threadIdx.x * 4; j < hidden; j += 1024) {
+        f32x4 v;
+        if (FROM_BF16) {
+            bf16x4 b = *reinterpret_cast<const bf16x4*>(ir + j);
+            v = __builtin_convertvector(b, f32x4);
+            *reinterpret_cast<f32x4*>(xr + j) = v;
+        } else {
+            v = *reinterpret_cast<const f32x4*>(xr + j);
+        }
+        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    }
+    float total = block_sum_256(ss, red);
+    float inv = 1.0f / sqrtf(total / (float)hidden + eps);
+    bf16_t* hr = h + row * ldh;
+    for (int j = threadIdx.x * 4; j < hidden; j += 1024) {
+        f32x4 v;
+        if (FROM_BF16) {
+            v = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(ir + j), f32x4);
+        } else {
+            v = *reinterpret_cast<const f32x4*>(xr + j);
+        }
+        f32x4 g = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(gamma + j), f32x4);
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = v[e] * inv * g[e];
+        *reinterpret_cast<bf16x4*>(hr + j) = __builtin_convertvector(o, bf16x4);
+    }
+}
+
+__global__ __launch_bounds__(256) void cast_out_kernel(const float* __restrict__ x, bf16_t* __restrict__ out,
+                                                        float* __restrict__ out_f32, int64_t count4) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count4) return;
+    f32x4 v = reinterpret_cast<const f32x4*>(x)[i];
+    reinterpret_cast<bf16x4*>(out)[i] = __builtin_convertvector(v, bf16x4);
+    if (out_f32) reinterpret_cast<f32x4*>(out_f32)[i] = v;
+}
+
+// dst[(dst_row0 + r)][c] = src[r][c] for c < cols; the padding is left as it is (zeroed by the caller).
+__global__ __launch_bounds__(256) void copy_rows_kernel(const bf16_t* __restrict__ src, int rows, int cols,
+                                                         bf16_t* __restrict__ dst, int64_t ld_dst, int dst_row0) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one 8-element group per thread
+    int groups = cols / 8;
+    if (i >= (int64_t)rows * groups) return;
+    int r = (int)(i / groups), g = (int)(i % groups);
+    *reinterpret_cast<u32x4*>(dst + (int64_t)(dst_row0 + r) * ld_dst + g * 8) =
+        *reinterpret_cast<const u32x4*>(src + (int64_t)r * cols + g * 8);
+}
+
+// Packed gate/up matrix: outputs are taken 32 at a time; packed rows 64b .. 64b+31 are the gate
+// rows 32b .. 32b+31, packed rows 64b+32 .. 64b+63 the matching up rows.
+__global__ __launch_bounds__(256) void pack_gate_up_kernel(const bf16_t* __restrict__ gate, const bf16_t* __restrict__ up,
+                                                            int inter, int hidden, bf16_t* __restrict__ dst,
+                                                            int64_t ld_dst) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int groups = hidden / 8;
+    if (i >= (int64_t)inter * groups) return;
+    int r = (int)(i / groups), g = (int)(i % groups);
+    int64_t prow = (int64_t)(r / kSwigluGroup) * (2 * kSwigluGroup) + r % kSwigluGroup;
+    *reinterpret_cast<u32x4*>(dst + prow * ld_dst + g * 8) =
+        *reinterpret_cast<const u32x4*>(gate + (int64_t)r * hidden + g * 8);
+    *reinterpret_cast<u32x4*>(dst + (prow + kSwigluGroup) * ld_dst + g * 8) =
+        *reinterpret_cast<const u32x4*>(up + (int64_t)r * hidden + g * 8);
+}
+
+// One workgroup per token row.  q heads and k heads are rotated (rotate-half pairing: element j
+// pairs with j + d/2, angle pos * theta^(-2j/d) taken from the table); k and v are rounded to
+// bf16 and stored at (page, slot = pos % 16) in the layer's pool:
+//   K element (head h, dim e) -> ((page*n_kv + h)*d*16) + (e/8)*128 + slot*8 + e%8
+//   V element (head h, dim e) -> ((page*n_kv + h)*d*16) + e*16 + slot
+__global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
+    const int t = blockIdx.x;
+    const int d = a.d, half = d / 2;
+    const int pos = a.tok_pos[t];
+    const int64_t page = a.tok_page[t];
+    const int slot = pos & (kPage - 1);
+    const float* row = a.qkv + (int64_t)t * a.ld_qkv;
+    const f32x2* cs = reinterpret_cast<const f32x2*>(a.rope_cs) + (int64_t)pos * half;
+    const int q_pairs = a.n_q * half, k_pairs = a.n_kv * half;
+    const int k_col0 = a.n_q * d, v_col0 = k_col0 + a.n_kv * d;
+    for (int i = threadIdx.x; i < q_pairs + k_pairs; i += 256) {
+        const bool is_q = i < q_pairs;
+        const int ii = is_q ? i : i - q_pairs;
+        const int hd = ii / half, j = ii % half;
+        const int col = (is_q ? 0 : k_col0) + hd * d + j;
+        float lo = row[col], hi = row[col + half];
+        if (a.bias) {
+            lo += (float)a.bias[col];
+            hi += (float)a.bias[col + half];
+        }
+        f32x2 c = cs[j];
+        float rlo = lo * c[0] - hi * c[1];
+        float rhi = hi * c[0] + lo * c[1];
+        if (is_q) {
+            bf16_t* q = a.q_out + (int64_t)t * a.ld_q + hd * d;
+            q[j] = (bf16_t)rlo;
+            q[j + half] = (bf16_t)rhi;
+        } else {
+            bf16_t* kb = a.k_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage);
+            int e0 = j, e1 = j + half;
+            kb[(e0 >> 3) * (kPage * 8) + slot * 8 + (e0 & 7)] = (bf16_t)rlo;
+            kb[(e1 >> 3) * (kPage * 8) + slot * 8 + (e1 & 7)] = (bf16_t)rhi;
+        }
+    }
+    const int v_elems = a.n_kv * d;
+    for (int i = threadIdx.x; i < v_elems; i += 256) {
+        const int hd = i / d, e = i % d;
+        float v = row[v_col0 + i];
+        if (a.bias) v += (float)a.bias[v_col0 + i];
+        bf16_t* vb = a.v_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage);
+        vb[e * kPage + slot] = (bf16_t)v;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_rmsnorm_from_bf16(const bf16_t* in, float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh,
+                                    int rows, int hidden, float eps, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    rmsnorm_kernel<true><<<rows, 256, 0, stream>>>(in, x, gamma, h, ldh, hidden, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm(const float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh, int rows, int hidden,
+                          float eps, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    rmsnorm_kernel<false><<<rows, 256, 0, stream>>>(nullptr, const_cast<float*>(x), gamma, h, ldh, hidden, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_cast_out(const float* x, bf16_t* out, float* out_f32, int64_t count, hipStream_t stream) {
+    if (count <= 0) return hipSuccess;
+    int64_t c4 = count / 4;
+    cast_out_kernel<<<(unsigned)ceil_div(c4, 256), 256, 0, stream>>>(x, out, out_f32, c4);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_rows_padded(const bf16_t* src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_row0,
+                                   hipStream_t stream) {
+    int64_t n = (int64_t)rows * (cols / 8);
+    if (n <= 0) return hipSuccess;
+    copy_rows_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(src, rows, cols, dst, ld_dst, dst_row0);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, int hidden, bf16_t* dst,
+                               int64_t ld_dst, hipStream_t stream) {
+    int64_t n = (int64_t)inter * (hidden / 8);
+    if (n <= 0) return hipSuccess;
+    pack_gate_up_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(gate, up, inter, hidden, dst, ld_dst);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_kv_write(const RopeKvArgs& a, hipStream_t stream) {
+    if (a.T <= 0) return hipSuccess;
+    rope_kv_write_kernel<<<a.T, 256, 0, stream>>>(a);
+    return hipGetLastError();
+}

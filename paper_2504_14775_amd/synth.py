@@ -357,3 +357,31 @@ def make_pool(shape: StageShape, seed: int, num_blocks: int, device="cpu",
             buf[start:start + cnt] = normal_bf16(seed, stream, start, cnt, sig, device=device)
         pools.append(buf)
     return pools[0], pools[1]
+
+
+# ----------------------------------------------------------------------------
+# sub-batches over a compact copy of the pages they use (for sampled checks of large batches)
+# ----------------------------------------------------------------------------
+def compact_subset(shape: StageShape, batch: Batch, seq_ids, new_tokens, k_pool: torch.Tensor,
+                   v_pool: torch.Tensor):
+    """Selects sequences (optionally only their first new tokens) and gathers the pages they own.
+
+    Rows of a sequence depend only on that sequence's own rows and pages, and the first m rows of a
+    chunk do not depend on its later rows, so the sub-batch reproduces those rows of the full batch.
+    Returns (sub_batch with pages renumbered 0..n-1, k_bits, v_bits, page_ids): the pools are host
+    uint16 arrays laid out [layer][page][...] like the originals; page_ids are the original ids.
+    """
+    sub = batch.subset(seq_ids, new_tokens)
+    ids: List[int] = []
+    bt = np.full_like(sub.block_tables, -1)
+    for s in range(sub.num_seqs):
+        nb = _pages(int(sub.new_tokens[s]) + int(sub.cached_len[s]))
+        bt[s, :nb] = np.arange(len(ids), len(ids) + nb)
+        ids += [int(x) for x in sub.block_tables[s, :nb]]
+    per_page = shape.n_kv_heads * shape.page_size * shape.head_dim
+    idx = torch.tensor(ids, dtype=torch.int64, device=k_pool.device)
+    out = []
+    for pool in (k_pool, v_pool):
+        view = pool.view(shape.num_layers, batch.num_blocks, per_page)
+        out.append(bf16_bits(view.index_select(1, idx)).reshape(-1).copy())
+    return Batch(sub.new_tokens, sub.cached_len, bt, len(ids), sub.label), out[0], out[1], np.array(ids)

@@ -38,3 +38,28 @@ def error_metrics(y, ref):
     ref = np.asarray(ref, dtype=np.float64)
     d = np.abs(y - ref)
     return float(d.max()), float(d.sum() / max(np.abs(ref).sum(), 1e-300)), float(np.sqrt((ref ** 2).mean()))
+
+
+def written_mask(shape, batch):
+    """Boolean mask over one flat K (or V) pool: True where this batch's new tokens must be stored.
+
+    Written from the interface's statement of the layout, independently of oracle and library:
+    position p of sequence s -> page block_tables[s][p // 16], slot p % 16, every layer, KV head and dim;
+    K element (dim e) at (e // 8) * 128 + slot * 8 + e % 8, V element at e * 16 + slot inside the
+    (page, head) block of head_dim * 16 elements.
+    """
+    ps, d, nkv = shape.page_size, shape.head_dim, shape.n_kv_heads
+    per_layer = synth.pool_elems_per_layer(shape, batch.num_blocks)
+    mk = np.zeros(shape.num_layers * per_layer, dtype=bool)
+    mv = np.zeros_like(mk)
+    e = np.arange(d)
+    for s in range(batch.num_seqs):
+        for i in range(int(batch.new_tokens[s])):
+            p = int(batch.cached_len[s]) + i
+            page, slot = int(batch.block_tables[s, p // ps]), p % ps
+            for l in range(shape.num_layers):
+                for h in range(nkv):
+                    base = l * per_layer + (page * nkv + h) * ps * d
+                    mk[base + (e // 8) * (ps * 8) + slot * 8 + e % 8] = True
+                    mv[base + e * ps + slot] = True
+    return mk, mv

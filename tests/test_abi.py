@@ -1,0 +1,59 @@
+"""The C-ABI library loads and exports every function include/gllm_stage.h declares (no GPU needed)."""
+import os
+import re
+
+import pytest
+
+from paper_2504_14775_amd import binding as B
+from paper_2504_14775_amd import synth
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "gllm_stage.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gllm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for n in ("gllm_stage_create", "gllm_stage_forward", "gllm_stage_load_layer", "gllm_stage_bind_kv_pool",
+              "gllm_stage_bind_workspace", "gllm_stage_destroy", "gllm_last_error"):
+        assert n in names
+
+
+def test_library_exports_every_declared_function():
+    lib = B.load_library()
+    for n in declared_functions():
+        assert hasattr(lib, n), n
+    assert set(B.EXPORTS) == set(declared_functions())
+
+
+def test_status_names_and_profile_classes():
+    lib = B.load_library()
+    for code, name in B.STATUS.items():
+        assert lib.gllm_status_name(code).decode() == name
+    n = lib.gllm_profile_num_classes()
+    names = [lib.gllm_profile_class_name(i).decode() for i in range(n)]
+    assert "gemm_gate_up_swiglu" in names and "attn_decode" in names and len(set(names)) == n
+
+
+def test_create_rejects_bad_configs_before_touching_a_device():
+    shape = synth.SHAPES["tiny"]
+    import dataclasses
+    for bad, status in [
+        (dict(page_size=8), -7),
+        (dict(head_dim=96), -7),
+        (dict(n_q_heads=5), -7),
+        (dict(hidden=200), -7),
+        (dict(num_layers=0), -1),
+    ]:
+        cfg = B.make_config(dataclasses.replace(shape, **bad), 64, 8, 8, 128)
+        with pytest.raises(B.GllmError) as e:
+            B.Stage(cfg)
+        assert e.value.status == status, (bad, e.value)
+    cfg = B.make_config(shape, 64, 8, 4, 128)          # 4 pages cannot hold 128 positions
+    with pytest.raises(B.GllmError) as e:
+        B.Stage(cfg)
+    assert e.value.status == -1

@@ -1,0 +1,78 @@
+"""GPU parity of the single operations exported by the C ABI against the oracle's steps."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_14775_amd import binding as B
+from paper_2504_14775_amd import synth
+from gpu_util import DEV, bits_of, to_dev_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_bits(seed, stream, shape, sigma):
+    n = int(np.prod(shape))
+    return synth.bf16_bits(synth.normal_bf16(seed, stream, 0, n, sigma)).reshape(shape)
+
+
+def padded_rows(bits, rows):
+    out = np.zeros((rows, bits.shape[1]), dtype=np.uint16)
+    out[: bits.shape[0]] = bits
+    return out
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (52, 512, 256), (300, 384, 192), (257, 1280, 704), (1024, 256, 2048)])
+def test_gemm_store_and_add(M, N, K):
+    print(f"gemm store/add M={M} N={N} K={K}", flush=True)
+    a = rand_bits(1, 1, (M, K), 1.0)
+    w = rand_bits(1, 2, (N, K), 0.05)
+    ref = oracle.linear(oracle.bf16_to_f64(a), w)
+    Mp = (M + 255) // 256 * 256
+    da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w)
+    out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= 2e-5 * scale + 1e-6
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32)
+    torch.cuda.synchronize()
+    got2 = out.cpu().numpy().astype(np.float64)
+    assert np.abs(got2 - 2 * ref).max() <= 4e-5 * scale + 1e-6
+
+
+@pytest.mark.parametrize("M,I,K", [(52, 768, 256), (130, 128, 128), (300, 1408, 320)])
+def test_gemm_swiglu(M, I, K):
+    print(f"gemm swiglu M={M} I={I} K={K}", flush=True)
+    a = rand_bits(2, 1, (M, K), 1.0)
+    wg = rand_bits(2, 2, (I, K), 0.08)
+    wu = rand_bits(2, 3, (I, K), 0.08)
+    x = oracle.bf16_to_f64(a)
+    ref = oracle.swiglu(oracle.linear(x, wg), oracle.linear(x, wu))
+    # interleave as the ABI states: groups of 64 rows = 32 gate rows then the 32 matching up rows
+    assert I % 128 == 0
+    packed = np.zeros((2 * I, K), dtype=np.uint16)
+    for blk in range(I // 32):
+        packed[64 * blk: 64 * blk + 32] = wg[32 * blk: 32 * blk + 32]
+        packed[64 * blk + 32: 64 * blk + 64] = wu[32 * blk: 32 * blk + 32]
+    Mp = (M + 255) // 256 * 256
+    out = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(packed), out, M, 2 * I, K, B.GEMM_SWIGLU_BF16)
+    torch.cuda.synchronize()
+    got = oracle.bf16_to_f64(bits_of(out))
+    err = np.abs(got - ref)
+    assert np.all(err <= np.abs(ref) * 2.0 ** -7 + 1e-4), float(err.max())
+
+
+@pytest.mark.parametrize("T,H", [(3, 256), (52, 4096), (17, 5120)])
+def test_rmsnorm(T, H):
+    print(f"rmsnorm T={T} H={H}", flush=True)
+    x = synth.normal_bf16(3, 1, 0, T * H, 2.0).to(torch.float32).reshape(T, H) * 1.37
+    gamma = rand_bits(3, 2, (H,), 0.5)
+    ref = oracle.rmsnorm(x.numpy().astype(np.float64), gamma, 1e-6)
+    h = torch.empty((T, H), dtype=torch.bfloat16, device=DEV)
+    B.gllm_op_rmsnorm(x.to(DEV), to_dev_bits(gamma), h, 1e-6)
+    torch.cuda.synchronize()
+    got = oracle.bf16_to_f64(bits_of(h))
+    assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 * 1.01 + 1e-6)
