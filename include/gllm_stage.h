@@ -158,15 +158,26 @@ const char* gllm_profile_class_name(int32_t i);
 
 /* out[m][n] (op)= sum_k a[m][k] * w[n][k];  a: bf16 [m_rows][lda] with lda >= k, w: bf16 [n][ldw].
  * Requirements: k a multiple of 64 and n a multiple of 128 (the stage pads its operands);
- * a must be readable for round_up(m,128) rows.  mode: 0 store fp32 to out[m][ldc];
+ * a must be readable for round_up(m,256) rows.  mode: 0 store fp32 to out[m][ldc];
  * 1 add into fp32 out[m][ldc]; 2 SwiGLU: columns come in groups of 64 = 32 gate + 32 up
- * outputs, out is bf16 [m][ldc] with n/2 columns, out = silu(gate) * up. */
+ * outputs, out is bf16 [m][ldc] with n/2 columns, out = silu(gate) * up.
+ * tile: -1 lets the library choose the workgroup tile; 0 = 128x128, 1 = 256x128, 2 = 256x256
+ * (4 wavefronts), 3 = 256x256 (8 wavefronts); a forced tile must divide n (GLLM_E_UNSUPPORTED otherwise). */
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
-                              int32_t m, int32_t n, int32_t k, int32_t mode, void* stream);
+                              int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream);
 
 /* h[t][j] = bf16(x[t][j] * rsqrt(mean_j x^2 + eps) * gamma[j]); x fp32 [rows][hidden]. */
 gllm_status gllm_op_rmsnorm(const float* x, const void* gamma_bf16, void* h_bf16, int32_t rows, int32_t hidden,
                             double eps, void* stream);
+
+/* Ceiling probes, used by the benchmark to report what this GPU sustains next to the published peaks
+ * (the paper gives no kernel-level figure; these are measurement aids, not part of the stage).
+ * peak_mfma: `workgroups` workgroups of 4 wavefronts, each wavefront issuing iters*16 independent
+ * 32x32x16 bf16 MFMAs (2*32*32*16 flop each) with no memory traffic.  peak_read: reads `bytes` of DEVICE
+ * memory once with 16-byte loads.  sink: DEVICE, at least 4 KiB; peak_mfma takes its operand bits from
+ * it (fill it with bf16 data of the kind the GEMMs see); it is never written in practice. */
+gllm_status gllm_op_peak_mfma(void* sink, int32_t workgroups, int32_t iters, void* stream);
+gllm_status gllm_op_peak_read(const void* src, int64_t bytes, void* sink, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

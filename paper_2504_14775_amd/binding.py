@@ -25,7 +25,7 @@ EXPORTS = [
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
     "gllm_stage_bind_kv_pool", "gllm_stage_set_alias_check", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
-    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_rmsnorm",
+    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
 ]
 
 
@@ -102,9 +102,13 @@ def load_library():
     lib.gllm_profile_class_name.restype = C.c_char_p
     lib.gllm_profile_class_name.argtypes = [i32]
     lib.gllm_op_gemm_bf16.restype = i32
-    lib.gllm_op_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, vp]
+    lib.gllm_op_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
     lib.gllm_op_rmsnorm.restype = i32
     lib.gllm_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_double, vp]
+    lib.gllm_op_peak_mfma.restype = i32
+    lib.gllm_op_peak_mfma.argtypes = [vp, i32, i32, vp]
+    lib.gllm_op_peak_read.restype = i32
+    lib.gllm_op_peak_read.argtypes = [vp, i64, vp, i32, vp]
     _lib = lib
     return lib
 
@@ -169,7 +173,7 @@ class Stage:
 
     def bind_kv_pool(self, k_pool, v_pool, num_blocks: int) -> None:
         self._check(self.lib.gllm_stage_bind_kv_pool(self.handle, k_pool.data_ptr(), v_pool.data_ptr(), num_blocks))
-        self._keep += [k_pool, v_pool]
+        self._pool = (k_pool, v_pool)
 
     def set_alias_check(self, on: bool) -> None:
         self._check(self.lib.gllm_stage_set_alias_check(self.handle, int(on)))
@@ -206,10 +210,11 @@ class Stage:
         return {self.lib.gllm_profile_class_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
-def gllm_op_gemm_bf16(a, w, out, m: int, n: int, k: int, mode: int, lda=None, ldw=None, ldc=None, stream=None):
+def gllm_op_gemm_bf16(a, w, out, m: int, n: int, k: int, mode: int, tile: int = -1, lda=None, ldw=None, ldc=None,
+                      stream=None):
     lib = load_library()
     st = lib.gllm_op_gemm_bf16(a.data_ptr(), lda or a.stride(0), w.data_ptr(), ldw or w.stride(0), out.data_ptr(),
-                               ldc or out.stride(0), m, n, k, mode, _stream_ptr(stream))
+                               ldc or out.stride(0), m, n, k, mode, tile, _stream_ptr(stream))
     if st != GLLM_OK:
         raise GllmError(st, "gllm_op_gemm_bf16")
 
@@ -220,6 +225,18 @@ def gllm_op_rmsnorm(x, gamma, h, eps: float, stream=None):
                              _stream_ptr(stream))
     if st != GLLM_OK:
         raise GllmError(st, "gllm_op_rmsnorm")
+
+
+def gllm_op_peak_mfma(sink, workgroups: int, iters: int, stream=None):
+    st = load_library().gllm_op_peak_mfma(sink.data_ptr(), workgroups, iters, _stream_ptr(stream))
+    if st != GLLM_OK:
+        raise GllmError(st, "gllm_op_peak_mfma")
+
+
+def gllm_op_peak_read(src, nbytes: int, sink, workgroups: int, stream=None):
+    st = load_library().gllm_op_peak_read(src.data_ptr(), nbytes, sink.data_ptr(), workgroups, _stream_ptr(stream))
+    if st != GLLM_OK:
+        raise GllmError(st, "gllm_op_peak_read")
 
 
 def stage_for_batches(shape, batches: Sequence, device="cuda"):

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgllm_stage.so")
 BUILD_DIR = os.path.join(HERE, "_build")
-SOURCES = ["gllm_stage.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_misc.hip"]
+SOURCES = ["gllm_stage.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_misc.hip", "kernels_peak.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

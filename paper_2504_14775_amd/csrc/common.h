@@ -31,17 +31,25 @@ enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 // ---- launchers (each enqueues on `stream` and returns the launch status) ----------------
 
 // out (op)= a[m x k] * w[n x k]^T, see gllm_op_gemm_bf16 in the public header.
+// tile: -1 picks a tile shape from m and n; 0..3 force one (128x128, 256x128, 256x256, 256x256 with 8 waves).
+// splits > 1 (store mode only): split s covers k range [s*k/splits, (s+1)*k/splits) and writes its partial
+// product to out + s*split_stride floats; the consumer sums the planes in order.
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,
-                            int m, int n, int k, int mode, hipStream_t stream);
+                            int m, int n, int k, int mode, int tile, int splits, int64_t split_stride,
+                            hipStream_t stream);
+int gemm_pick_tile(int m, int n, int splits);
+int gemm_pick_splits(int m, int n, int k);
 
 // Residual stream entry: x = float(in_bf16), h = bf16(rmsnorm(x) * gamma).
 hipError_t launch_rmsnorm_from_bf16(const bf16_t* in, float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh,
                                     int rows, int hidden, float eps, hipStream_t stream);
-// h = bf16(rmsnorm(x) * gamma) from the fp32 residual stream.
-hipError_t launch_rmsnorm(const float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh, int rows, int hidden,
-                          float eps, hipStream_t stream);
-// out_bf16 = RNE(x), and optionally a copy of x.
-hipError_t launch_cast_out(const float* x, bf16_t* out, float* out_f32, int64_t count, hipStream_t stream);
+// x += y[0] + ... + y[planes-1] (planes may be 0; plane p at y + p*plane_stride), then
+// h = bf16(rmsnorm(x) * gamma).  x is updated in place when planes > 0.
+hipError_t launch_add_rmsnorm(float* x, const float* y, int planes, int64_t plane_stride, const bf16_t* gamma,
+                              bf16_t* h, int64_t ldh, int rows, int hidden, float eps, hipStream_t stream);
+// out_bf16 = RNE(x + y planes), and optionally out_f32 = that sum.
+hipError_t launch_add_cast_out(const float* x, const float* y, int planes, int64_t plane_stride, bf16_t* out,
+                               float* out_f32, int64_t count, hipStream_t stream);
 
 // Weight repacking (device to device).
 hipError_t launch_copy_rows_padded(const bf16_t* src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_row0,
@@ -103,3 +111,8 @@ struct PrefillItem {
     int32_t bt_off;    // offset of the sequence's first page id in bt_flat
 };
 hipError_t launch_prefill_attention(const AttnArgs& a, const PrefillItem* items, int num_items, hipStream_t stream);
+
+// Ceiling probes (see kernels_peak.hip).  peak_mfma: workgroups x 4 waves x iters x 16 MFMAs of
+// 2*32*32*16 flop each.  peak_read: reads `bytes` once.
+hipError_t launch_peak_mfma(float* sink, int workgroups, int iters, hipStream_t stream);
+hipError_t launch_peak_read(const void* src, int64_t bytes, void* sink, int workgroups, hipStream_t stream);

@@ -4,8 +4,10 @@
 // shared by all layers because every layer uses the same page tables, paper section 3.4),
 // uploads it with one asynchronous copy from pinned staging, and enqueues, per layer:
 //   RMSNorm -> QKV GEMM -> RoPE + paged KV write -> prefill attention, decode attention (+merge)
-//   -> O GEMM (+= residual) -> RMSNorm -> gate/up GEMM (SwiGLU) -> down GEMM (+= residual)
-// and finally the cast of the fp32 residual stream to bf16.  Nothing in the call waits for the
+//   -> O GEMM -> residual add + RMSNorm -> gate/up GEMM (SwiGLU) -> down GEMM -> (residual add fused into the
+//   next layer's RMSNorm)
+// and finally the last residual add with the cast of the fp32 residual stream to bf16.  The O and down
+// projections may be split along k; their partial products are summed in fixed order by the consumer.  Nothing in the call waits for the
 // device, so consecutive batches queue back to back (the host-side preparation of batch i+1
 // overlaps the execution of batch i, the "metadata ahead of data" idea of section 3.4).
 #include "../../include/gllm_stage.h"
@@ -37,6 +39,7 @@ struct LayerBuffers {
 
 constexpr int kStagingSlots = 4;
 constexpr int kPrefillTileRows = 64;
+constexpr int kMaxSplits = 4;
 
 struct MetaLayout {  // offsets in bytes inside the metadata block (host staging and device copy alike)
     size_t tok_pos, tok_page, bt_flat, dec_items, dec_rows, pre_items, total;
@@ -65,6 +68,7 @@ struct gllm_stage {
     bf16_t* act = nullptr;
     float* part_o = nullptr;
     float* part_ml = nullptr;
+    float* y = nullptr;  // [kMaxSplits][max_tokens][hidden] partial outputs of the O / down projections
     // pool
     bf16_t *k_pool = nullptr, *v_pool = nullptr;
     int64_t num_blocks = 0;
@@ -118,6 +122,7 @@ size_t workspace_layout(gllm_stage* s, unsigned char* base) {
     s->act = (bf16_t*)take((size_t)s->m_pad * s->inter_pad * 2);
     s->part_o = (float*)take((size_t)s->max_items * c.n_q_heads * c.head_dim * 4);
     s->part_ml = (float*)take((size_t)s->max_items * c.n_q_heads * 2 * 4);
+    s->y = (float*)take((size_t)kMaxSplits * c.max_tokens * c.hidden * 4);
     return off;
 }
 
@@ -508,16 +513,20 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     const int Ti = (int)T, H = c.hidden, d = c.head_dim;
     const int64_t pool_layer = (int64_t)s->num_blocks * c.n_kv_heads * kPage * d;
     const float eps = (float)c.rms_eps;
+    const int64_t y_plane = (int64_t)c.max_tokens * H;
+    const int split_o = std::min(kMaxSplits, gemm_pick_splits(Ti, H, s->q_dim));
+    const int split_d = std::min(kMaxSplits, gemm_pick_splits(Ti, H, s->inter_pad));
+    int pending = 0;  // planes of y still to be added to the residual stream
     for (int l = 0; l < c.num_layers; ++l) {
         const LayerBuffers& L = s->layers[l];
         {
             ProfScope ps(s, st, PC_RMSNORM);
             if (l == 0) HIP_TRY(s, launch_rmsnorm_from_bf16((const bf16_t*)hidden_in, s->x, L.norm1, s->h, H, Ti, H, eps, st));
-            else HIP_TRY(s, launch_rmsnorm(s->x, L.norm1, s->h, H, Ti, H, eps, st));
+            else HIP_TRY(s, launch_add_rmsnorm(s->x, s->y, pending, y_plane, L.norm1, s->h, H, Ti, H, eps, st));
         }
         {
             ProfScope ps(s, st, PC_GEMM_QKV);
-            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wqkv, H, s->qkv, s->n_qkv_pad, Ti, s->n_qkv_pad, H, GEMM_STORE_F32, st));
+            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wqkv, H, s->qkv, s->n_qkv_pad, Ti, s->n_qkv_pad, H, GEMM_STORE_F32, -1, 1, 0, st));
         }
         {
             ProfScope ps(s, st, PC_ROPE_KV);
@@ -549,41 +558,53 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
             HIP_TRY(s, launch_decode_combine(aa, d_rows, n_rows, s->part_o, s->part_ml, st));
         }
         {
+            // the projection writes split_o partial products; the next RMSNorm adds them to the residual stream
             ProfScope ps(s, st, PC_GEMM_O);
-            HIP_TRY(s, launch_gemm_bf16(s->attn, s->q_dim, L.wo, s->q_dim, s->x, H, Ti, H, s->q_dim, GEMM_ADD_F32, st));
+            HIP_TRY(s, launch_gemm_bf16(s->attn, s->q_dim, L.wo, s->q_dim, s->y, H, Ti, H, s->q_dim, GEMM_STORE_F32, -1, split_o, y_plane, st));
         }
         {
             ProfScope ps(s, st, PC_RMSNORM);
-            HIP_TRY(s, launch_rmsnorm(s->x, L.norm2, s->h, H, Ti, H, eps, st));
+            HIP_TRY(s, launch_add_rmsnorm(s->x, s->y, split_o, y_plane, L.norm2, s->h, H, Ti, H, eps, st));
         }
         {
             ProfScope ps(s, st, PC_GEMM_GATEUP);
-            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wgu, H, s->act, s->inter_pad, Ti, 2 * s->inter_pad, H, GEMM_SWIGLU_BF16, st));
+            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wgu, H, s->act, s->inter_pad, Ti, 2 * s->inter_pad, H, GEMM_SWIGLU_BF16, -1, 1, 0, st));
         }
         {
             ProfScope ps(s, st, PC_GEMM_DOWN);
-            HIP_TRY(s, launch_gemm_bf16(s->act, s->inter_pad, L.wd, s->inter_pad, s->x, H, Ti, H, s->inter_pad, GEMM_ADD_F32, st));
+            HIP_TRY(s, launch_gemm_bf16(s->act, s->inter_pad, L.wd, s->inter_pad, s->y, H, Ti, H, s->inter_pad, GEMM_STORE_F32, -1, split_d, y_plane, st));
         }
+        pending = split_d;
     }
     {
         ProfScope ps(s, st, PC_CAST);
-        HIP_TRY(s, launch_cast_out(s->x, (bf16_t*)hidden_out, hidden_out_f32, (int64_t)Ti * H, st));
+        HIP_TRY(s, launch_add_cast_out(s->x, s->y, pending, y_plane, (bf16_t*)hidden_out, hidden_out_f32, (int64_t)Ti * H, st));
     }
     return GLLM_OK;
 }
 
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
-                              int32_t m, int32_t n, int32_t k, int32_t mode, void* stream) {
+                              int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream) {
     if (!a || !w || !out) return GLLM_E_INVALID;
-    hipError_t e = launch_gemm_bf16((const bf16_t*)a, lda, (const bf16_t*)w, ldw, out, ldc, m, n, k, mode, (hipStream_t)stream);
+    hipError_t e = launch_gemm_bf16((const bf16_t*)a, lda, (const bf16_t*)w, ldw, out, ldc, m, n, k, mode, tile, 1, 0, (hipStream_t)stream);
     return e == hipSuccess ? GLLM_OK : (e == hipErrorInvalidValue ? GLLM_E_UNSUPPORTED : GLLM_E_HIP);
 }
 
 gllm_status gllm_op_rmsnorm(const float* x, const void* gamma, void* h, int32_t rows, int32_t hidden, double eps,
                             void* stream) {
     if (!x || !gamma || !h || hidden % 4 != 0) return GLLM_E_INVALID;
-    hipError_t e = launch_rmsnorm(x, (const bf16_t*)gamma, (bf16_t*)h, hidden, rows, hidden, (float)eps, (hipStream_t)stream);
+    hipError_t e = launch_add_rmsnorm(const_cast<float*>(x), nullptr, 0, 0, (const bf16_t*)gamma, (bf16_t*)h, hidden, rows, hidden, (float)eps, (hipStream_t)stream);
     return e == hipSuccess ? GLLM_OK : GLLM_E_HIP;
+}
+
+gllm_status gllm_op_peak_mfma(void* sink, int32_t workgroups, int32_t iters, void* stream) {
+    if (!sink || workgroups < 1 || iters < 1) return GLLM_E_INVALID;
+    return launch_peak_mfma((float*)sink, workgroups, iters, (hipStream_t)stream) == hipSuccess ? GLLM_OK : GLLM_E_HIP;
+}
+
+gllm_status gllm_op_peak_read(const void* src, int64_t bytes, void* sink, int32_t workgroups, void* stream) {
+    if (!src || !sink || bytes < 16 || workgroups < 1) return GLLM_E_INVALID;
+    return launch_peak_read(src, bytes, sink, workgroups, (hipStream_t)stream) == hipSuccess ? GLLM_OK : GLLM_E_HIP;
 }
 
 }  // extern "C"

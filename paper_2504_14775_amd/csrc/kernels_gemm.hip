@@ -2,18 +2,24 @@
 //
 // Both operands are contiguous along k, which is the order the MFMA operand registers want
 // (each lane feeds 8 consecutive k of one row), so tiles go global -> LDS -> registers without
-// any transposition.  One workgroup of 4 wavefronts (2 x 2) owns a BM x BN output tile and walks
-// k in steps of 64 through two LDS buffers: the global loads of step i+1 are issued before the
-// MFMAs of step i and written to the other buffer afterwards.
+// any transposition.  A workgroup of WGM x WGN wavefronts owns a BM x BN output tile and walks k
+// in steps of 64 through two LDS stages.  Tiles are brought in with global_load_lds (16 bytes per
+// lane straight into LDS, no staging registers): the loads of step i+1 are issued right after the
+// barrier that ends step i-1 and complete under the MFMAs of step i.
 //
-// LDS tile layout: row r holds its 64 k-values as eight 16-byte groups; group c is stored at
-// group position c ^ (r & 7).  A wavefront's 16-byte operand reads (32 rows x 2 groups) and the
-// loader's 16-byte writes then spread evenly over the banks.
+// LDS stage layout: rows of 64 k-values (128 bytes = eight 16-byte groups), A rows first, then W
+// rows.  Two consecutive rows form a 256-byte line of 16 group positions (the width of the 64 LDS
+// banks); group c of row r sits at position ((r & 1) * 8 + c) ^ ((r >> 1) & 7) of line r >> 1.  The
+// 16-byte operand reads of the MFMA loop take, per 16 lanes, one group index of 16 consecutive rows:
+// with this placement those 16 reads fall into 16 different bank groups (measured: the plain
+// c ^ (r & 7) placement costs a 2-way bank conflict on every read).  A global_load_lds instruction
+// fills 1 KiB = 4 lines: lane l owns position l % 16 of line l / 16 and fetches the global group that
+// belongs there; the 16 lanes of a line still cover the full 128 bytes of both of its rows.
 //
 // Workgroup -> tile mapping: hardware hands consecutive workgroup ids to the 8 XCDs in turn, each
-// with its own L2.  Ids are therefore first regrouped so that an XCD receives a contiguous range of
-// tile numbers; tiles are numbered band by band (a band is 8 tile-columns wide, walked row by row),
-// so the tiles an XCD works on at one time share a few A row-panels and W row-panels in its L2.
+// with its own L2.  Ids are first regrouped so that an XCD receives a contiguous range of tile
+// numbers; tiles are numbered band by band (a band is 8 tile-columns wide, walked row by row), so
+// the tiles an XCD works on at one time share a few A row-panels and W row-panels in its L2.
 #include "common.h"
 
 namespace {
@@ -22,18 +28,24 @@ constexpr int BK = 64;
 
 __device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int BM, int BN, int MODE>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                         const bf16_t* __restrict__ W, int64_t ldw,
-                                                         void* __restrict__ out, int64_t ldc, int M, int N, int K,
-                                                         int tiles_m, int tiles_n) {
-    constexpr int TM = BM / 64;  // 32x32 blocks per wave along m
-    constexpr int TN = BN / 64;
-    constexpr int A_CHUNKS = BM / 32;  // 16-byte groups each thread moves per k-step
-    constexpr int W_CHUNKS = BN / 32;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* lds_a = reinterpret_cast<bf16_t*>(smem);                       // [2][BM][64]
-    bf16_t* lds_w = lds_a + 2 * BM * BK;                                   // [2][BN][64]
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                    const bf16_t* __restrict__ W, int64_t ldw,
+                                                                    void* __restrict__ out, int64_t ldc, int M,
+                                                                    int N, int K, int tiles_m, int tiles_n, int64_t split_stride,
+                                                                    int dbg) {
+    constexpr int NW = WGM * WGN;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
+    constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
+    constexpr int GROUPS = (BM + BN) / 8;          // 1 KiB load groups per stage
+    constexpr int GPW = GROUPS / NW;               // groups per wave
+    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    static_assert(GROUPS % NW == 0 && NW % 2 == 0, "load groups must divide among an even number of waves");
+    static_assert(MODE != GEMM_SWIGLU_BF16 || TN % 2 == 0, "SwiGLU needs gate and up blocks in one wave");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // ---- tile assignment (XCD aware) ----
     const int num_tiles = tiles_m * tiles_n;
@@ -52,31 +64,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     const int tile_n = band * BAND + in_band % band_cols;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
 
-    // ---- loader addressing: thread moves group c of rows r0 + 32 i ----
-    const int c = tid & 7, r0 = tid >> 3;
-    const bf16_t* ga = A + (int64_t)(m0 + r0) * lda + c * 8;
-    const bf16_t* gw = W + (int64_t)(n0 + r0) * ldw + c * 8;
-    const int lds_off = r0 * BK + ((c ^ (r0 & 7)) * 8);
+    // split-K: blockIdx.y owns a contiguous share of the k range and its own output plane
+    const int KT = (K / BK) / (int)gridDim.y;
+    const int kt_base = blockIdx.y * KT;
+    const int64_t split_off = (int64_t)blockIdx.y * split_stride;
 
-    u32x4 ra[A_CHUNKS], rw[W_CHUNKS];
-    auto load_global = [&](int kt) {
-        const int64_t k0 = (int64_t)kt * BK;
+    // ---- loader: wave w fills groups w, w + NW, ...; lane offsets are the same for every group ----
+    // group g covers rows 8g .. 8g+7 = lines 4g .. 4g+3; NW is even, so g has the parity of `wave`
+    const int lline = lane >> 4;
+    const int lq = (lane & 15) ^ ((4 * (wave & 1) + lline) & 7);
+    const int lrow = 2 * lline + (lq >> 3), lgrp = lq & 7;
+    const uint32_t voff_a = (uint32_t)(lrow * lda + lgrp * 8) * 2u;
+    const uint32_t voff_w = (uint32_t)(lrow * ldw + lgrp * 8) * 2u;
+    const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+    const char* w_tile = reinterpret_cast<const char*>(W + (int64_t)n0 * ldw);
+    auto issue_loads = [&](int kt, int stage) {
+        if ((dbg & 1) && kt > 1) return;  // timing experiment: no global loads after the first two tiles
+        if (dbg & 2) kt = 0;              // timing experiment: always the same k-slice (all cache hits)
+        kt += kt_base;
+        unsigned char* sbase = smem + stage * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) ra[i] = *reinterpret_cast<const u32x4*>(ga + (int64_t)(32 * i) * lda + k0);
-#pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) rw[i] = *reinterpret_cast<const u32x4*>(gw + (int64_t)(32 * i) * ldw + k0);
-    };
-    auto store_lds = [&](int buf) {
-        bf16_t* pa = lds_a + buf * BM * BK + lds_off;
-        bf16_t* pw = lds_w + buf * BN * BK + lds_off;
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4*>(pa + 32 * i * BK) = ra[i];
-#pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<u32x4*>(pw + 32 * i * BK) = rw[i];
+        for (int i = 0; i < GPW; ++i) {
+            const int g = wave + i * NW;  // wave-uniform
+            if (g < BM / 8) {
+                const char* src = a_tile + ((int64_t)(g * 8) * lda + (int64_t)kt * BK) * 2 + voff_a;
+                __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sbase + g * 1024), 16, 0, 0);
+            } else {
+                const char* src = w_tile + ((int64_t)(g * 8 - BM) * ldw + (int64_t)kt * BK) * 2 + voff_w;
+                __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sbase + g * 1024), 16, 0, 0);
+            }
+        }
     };
 
     f32x16 acc[TM][TN];
@@ -87,81 +108,146 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // operand read addressing: lane supplies row (lane % 32), k-group (lane / 32) of each 16-wide k step
-    const int frow = lane & 31, fgrp = lane >> 5, fsw = lane & 7;
-    const int a_row_off = (wm * (BM / 2) + frow) * BK;
-    const int w_row_off = (wn * (BN / 2) + frow) * BK;
-
-    const int KT = K / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_global(kt + 1);
-        const bf16_t* pa = lds_a + buf * BM * BK + a_row_off;
-        const bf16_t* pw = lds_w + buf * BN * BK + w_row_off;
+    // operand reads: lane supplies row (lane % 32), k-group (lane / 32) of each 16-wide k step
+    const int frow = lane & 31, fgrp = lane >> 5, fsw = (frow >> 1) & 7, fpar = (frow & 1) * 8;
+    const int a_off = (wm * WTM + (frow & ~1)) * (BK * 2);
+    const int w_off = (BM + wn * WTN + (frow & ~1)) * (BK * 2);
+    bf16x8 fa[2][TM], fw[2][TN];
+    auto load_frags = [&](int stage, int kk, int buf) {
+        const unsigned char* sa = smem + stage * STAGE_BYTES + a_off;
+        const unsigned char* sw = smem + stage * STAGE_BYTES + w_off;
+        const int g = ((fpar + kk * 2 + fgrp) ^ fsw) * 16;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int g = ((kk * 2 + fgrp) ^ fsw) * 8;
-            bf16x8 fa[TM], fw[TN];
+        for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * (BK * 2) + g);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(pa + i * 32 * BK + g);
+        for (int j = 0; j < TN; ++j) fw[buf][j] = *reinterpret_cast<const bf16x8*>(sw + j * 32 * (BK * 2) + g);
+    };
+    auto mfmas = [&](int buf) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fw[j] = *reinterpret_cast<const bf16x8*>(pw + j * 32 * BK + g);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fw[buf][j], acc[i][j], 0, 0, 0);
+    };
+    // scheduling hint for one "fetch fragments of the next k-step, multiply the current one" step:
+    // spread the LDS reads between the MFMAs so that their latency is covered
+    constexpr int kReads = TM + TN, kMfma = TM * TN;
+    constexpr int kPaired = kReads < kMfma ? kReads : kMfma;
+    auto interleave = [&]() {
+        // reads first, one per MFMA, so that the MFMAs left over cover the latency of the last read
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fw[j], acc[i][j], 0, 0, 0);
+        for (int r = 0; r < kPaired; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA (first, so that the wait for the
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // previous reads precedes every new read)
         }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
-        __syncthreads();
+        __builtin_amdgcn_sched_group_barrier(0x100, kReads - kPaired, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kPaired, 0);
+    };
+
+    // Software pipeline.  Global: tile kt+1 is in flight while tile kt is multiplied.  LDS -> registers:
+    // the fragments of k-step kk+1 are fetched while k-step kk is multiplied, also across the tile
+    // boundary: the barrier sits before the last k-step of a tile, after which the next tile's first
+    // fragments are fetched under the MFMAs of that last k-step.
+    constexpr int KK = BK / 16;
+    issue_loads(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (KT > 1) issue_loads(1, 1);
+    load_frags(0, 0, 0);
+    for (int kt = 0; kt < KT; ++kt) {
+        const int stage = kt & 1;
+#pragma unroll
+        for (int kk = 0; kk < KK - 1; ++kk) {
+            if (!(DBG & 1)) load_frags(stage, kk + 1, (kk + 1) & 1);
+            mfmas(kk & 1);
+            interleave();
+        }
+        if (kt + 1 < KT) {
+            if (!(DBG & 2)) {
+                if (!(DBG & 4)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();  // tile kt+1 has landed everywhere; every wave holds its last fragments of tile kt
+            }
+            if (kt + 2 < KT) issue_loads(kt + 2, stage);
+            if (!(DBG & 1)) load_frags(stage ^ 1, 0, KK & 1);
+        }
+        mfmas((KK - 1) & 1);
+        if (kt + 1 < KT) interleave();
     }
 
-    // ---- epilogue.  Accumulator element v of a 32x32 block: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+    if (DBG & 8) {  // timing experiment: no epilogue (one store keeps the accumulators alive)
+        float s0 = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) s0 += acc[i][j][0] + acc[i][j][7];
+        if (s0 == 1234.5f) reinterpret_cast<float*>(out)[0] = s0;
+        return;
+    }
+
+    // ---- epilogue, staged through LDS so that every global access is a 16-byte piece of a long row
+    // segment.  Accumulator element v of a 32x32 block sits at row 8*(v/4) + 4*(lane/32) + v%4, column
+    // lane%32; a wave writes one 32-row slab of its tile to its private LDS area, then reads it back row
+    // by row, 4 consecutive columns per lane.
+    constexpr int C = (MODE == GEMM_SWIGLU_BF16) ? WTN / 2 : WTN;  // result columns of a wave slab
+    constexpr int CS = C + 8;                                       // padded row stride (floats)
+    constexpr int LPR = C / 4;                                      // lanes per row on the way out
+    constexpr int RPI = 64 / LPR;                                   // rows per read instruction
+    static_assert(NW * 32 * CS * 4 <= 2 * STAGE_BYTES, "epilogue slab must fit in the tile buffers");
+    float* slab = reinterpret_cast<float*>(smem) + wave * (32 * CS);
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+    const int orow = lane / LPR, ocol = (lane % LPR) * 4;
+    __syncthreads();  // all waves have finished reading the last tile
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int mb = m0 + wm * (BM / 2) + i * 32 + row_in;
         if (MODE == GEMM_SWIGLU_BF16) {
             // block columns alternate gate (even j) / up (odd j) for the same 32 outputs
 #pragma unroll
-            for (int j = 0; j < TN; j += 2) {
-                const int n_packed = n0 + wn * (BN / 2) + j * 32;
-                const int oc = n_packed / 2 + col_in;
-                bf16_t* o = reinterpret_cast<bf16_t*>(out);
+            for (int j = 0; j < TN; j += 2)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = mb + 8 * (v / 4) + (v % 4);
-                    if (m < M) o[(int64_t)m * ldc + oc] = (bf16_t)(silu(acc[i][j][v]) * acc[i][j + 1][v]);
-                }
-            }
+                for (int v = 0; v < 16; ++v)
+                    slab[(8 * (v / 4) + row_in + (v % 4)) * CS + (j / 2) * 32 + col_in] =
+                        silu(acc[i][j][v]) * acc[i][j + 1][v];
         } else {
-            float* o = reinterpret_cast<float*>(out);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + col_in;
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = mb + 8 * (v / 4) + (v % 4);
-                    if (m < M) {
-                        float* p = o + (int64_t)m * ldc + n;
-                        if (MODE == GEMM_ADD_F32) *p += acc[i][j][v];
-                        else *p = acc[i][j][v];
+                for (int v = 0; v < 16; ++v)
+                    slab[(8 * (v / 4) + row_in + (v % 4)) * CS + j * 32 + col_in] = acc[i][j][v];
+        }
+        __syncthreads();
+        const int mrow0 = m0 + wm * WTM + i * 32;
+#pragma unroll
+        for (int r = 0; r < 32; r += RPI) {
+            const int m = mrow0 + r + orow;
+            const f32x4 val = *reinterpret_cast<const f32x4*>(slab + (r + orow) * CS + ocol);
+            if (m < M) {
+                if (MODE == GEMM_SWIGLU_BF16) {
+                    bf16_t* p = reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldc + (n0 + wn * WTN) / 2 + ocol;
+                    *reinterpret_cast<bf16x4*>(p) = __builtin_convertvector(val, bf16x4);
+                } else {
+                    float* p = reinterpret_cast<float*>(out) + split_off + (int64_t)m * ldc + n0 + wn * WTN + ocol;
+                    if (MODE == GEMM_ADD_F32) {
+                        f32x4 old = *reinterpret_cast<const f32x4*>(p);
+                        *reinterpret_cast<f32x4*>(p) = old + val;
+                    } else {
+                        *reinterpret_cast<f32x4*>(p) = val;
                     }
                 }
             }
         }
+        __syncthreads();
     }
 }
 
-template <int BM, int BN, int MODE>
+int g_gemm_debug = 0;
+
+template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
-                       int n, int k, hipStream_t stream) {
+                       int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
+    if (n % BN != 0) return hipErrorInvalidValue;
     const int tiles_m = (int)ceil_div(m, BM), tiles_n = n / BN;
     const size_t smem = 2 * (BM + BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, MODE>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, DBG>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -169,26 +255,73 @@ hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<tiles_m * tiles_n, 256, smem, stream>>>(a, lda, w, ldw, out, ldc, m, n, k, tiles_m, tiles_n);
+    kern<<<dim3(tiles_m * tiles_n, splits), 64 * WGM * WGN, smem, stream>>>(a, lda, w, ldw, out, ldc, m, n, k, tiles_m,
+                                                                          tiles_n, split_stride, g_gemm_debug);
     return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
-                       int n, int k, hipStream_t stream) {
-    return launch_tile<128, 128, MODE>(a, lda, w, ldw, out, ldc, m, n, k, stream);
+                       int n, int k, int tile, int splits, int64_t split_stride, hipStream_t stream) {
+#define GLLM_TILE_ARGS a, lda, w, ldw, out, ldc, m, n, k, splits, split_stride, stream
+    switch (tile) {
+        case 0: return launch_tile<128, 128, 2, 2, MODE>(GLLM_TILE_ARGS);
+        case 1: return launch_tile<256, 128, 2, 2, MODE>(GLLM_TILE_ARGS);
+        case 2: return launch_tile<256, 256, 2, 2, MODE>(GLLM_TILE_ARGS);
+        case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
+        case 8: return launch_tile<256, 256, 2, 2, MODE, 1>(GLLM_TILE_ARGS);
+        case 9: return launch_tile<256, 256, 2, 2, MODE, 2>(GLLM_TILE_ARGS);
+        case 10: return launch_tile<256, 256, 2, 2, MODE, 3>(GLLM_TILE_ARGS);
+        case 11: return launch_tile<256, 256, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
+        case 12: return launch_tile<256, 256, 2, 2, MODE, 8>(GLLM_TILE_ARGS);
+        case 13: return launch_tile<256, 256, 2, 2, MODE, 12>(GLLM_TILE_ARGS);
+        case 14: return launch_tile<256, 256, 2, 2, MODE, 11>(GLLM_TILE_ARGS);
+        default: return hipErrorInvalidValue;
+    }
+#undef GLLM_TILE_ARGS
 }
 
 }  // namespace
 
+// Tile shape for a problem: the 256x256 tile (8 waves) feeds the matrix cores best, but a launch
+// should offer every compute unit work; when the big tile yields too few workgroups the 128x128 tile
+// (two workgroups per compute unit) fills the chip better.
+int gemm_pick_tile(int m, int n, int splits) {
+    if (n % 256 != 0) return 0;
+    const int64_t big = ceil_div(m, 256) * (int64_t)(n / 256) * splits;
+    if (big >= 160) return 3;
+    const int64_t small = ceil_div(m, 128) * (int64_t)(n / 128) * splits;
+    return (small > big * 2 || big < 96) ? 0 : 3;
+}
+
+// Split-K factor for a GEMM whose consumer can sum partial outputs: enough workgroups to give every
+// compute unit a 256x256 tile, as long as each share of k keeps at least 16 steps of 64.
+int gemm_pick_splits(int m, int n, int k) {
+    if (n % 256 != 0) return 1;
+    const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 256);
+    int s = 1;
+    while (s < 4 && tiles * s < 192 && (k / BK) % (s * 2) == 0 && (k / BK) / (s * 2) >= 16) s *= 2;
+    return s;
+}
+
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,
-                            int m, int n, int k, int mode, hipStream_t stream) {
+                            int m, int n, int k, int mode, int tile, int splits, int64_t split_stride,
+                            hipStream_t stream) {
     if (m <= 0) return hipSuccess;
     if (n <= 0 || k <= 0 || n % 128 != 0 || k % BK != 0) return hipErrorInvalidValue;
+    if (lda * 16 >= (int64_t)1 << 31 || ldw * 16 >= (int64_t)1 << 31) return hipErrorInvalidValue;
+    if (splits < 1 || (k / BK) % splits != 0) return hipErrorInvalidValue;
+    if (splits > 1 && mode != GEMM_STORE_F32) return hipErrorInvalidValue;
+    g_gemm_debug = tile >= 0 ? tile >> 4 : 0;  // bits 4.. of a forced tile id select timing experiments
+    if (tile >= 0) tile &= 15;
+    if (tile < 0) tile = gemm_pick_tile(m, n, splits);
     switch (mode) {
-        case GEMM_STORE_F32: return launch_mode<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, stream);
-        case GEMM_ADD_F32: return launch_mode<GEMM_ADD_F32>(a, lda, w, ldw, out, ldc, m, n, k, stream);
-        case GEMM_SWIGLU_BF16: return launch_mode<GEMM_SWIGLU_BF16>(a, lda, w, ldw, out, ldc, m, n, k, stream);
+        case GEMM_STORE_F32:
+            return launch_mode<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, tile, splits, split_stride, stream);
+        case GEMM_ADD_F32:
+            return launch_mode<GEMM_ADD_F32>(a, lda, w, ldw, out, ldc, m, n, k, tile, splits, split_stride, stream);
+        case GEMM_SWIGLU_BF16:
+            return launch_mode<GEMM_SWIGLU_BF16>(a, lda, w, ldw, out, ldc, m, n, k, tile, splits, split_stride, stream);
         default: return hipErrorInvalidValue;
     }
 }

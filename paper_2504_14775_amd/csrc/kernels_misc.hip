@@ -22,51 +22,61 @@ __device__ __forceinline__ float block_sum_256(float v, float* red /*[4]*/) {
     return t;
 }
 
-// One workgroup per row.  FROM_BF16: the row comes from the bf16 stage input and is also
-// written out as the fp32 residual stream.
-template <bool FROM_BF16>
+// One workgroup per row.  FROM_BF16: the row comes from the bf16 stage input and is also written out
+// as the fp32 residual stream.  Otherwise the row is the fp32 residual stream plus `planes` partial
+// GEMM outputs (summed in plane order and written back), so the residual add costs no extra pass.
+// The row is kept in registers between the two phases (MAXV 16-byte pieces per thread).
+template <bool FROM_BF16, int MAXV>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t* __restrict__ in, float* __restrict__ x,
+                                                       const float* __restrict__ y, int planes, int64_t plane_stride,
                                                        const bf16_t* __restrict__ gamma, bf16_t* __restrict__ h,
                                                        int64_t ldh, int hidden, float eps) {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
     float* xr = x + row * hidden;
-    const bf16_t* ir = FROM_BF16 ? in + row * hidden : nullptr;
+    f32x4 keep[MAXV];
     float ss = 0.f;
-    for (int j = threadIdx.x * 4; j < hidden; j += 1024) {
-        f32x4 v;
-        if (FROM_BF16) {
-            bf16x4 b = *reinterpret_cast<const bf16x4*>(ir + j);
-            v = __builtin_convertvector(b, f32x4);
-            *reinterpret_cast<f32x4*>(xr + j) = v;
-        } else {
-            v = *reinterpret_cast<const f32x4*>(xr + j);
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int j = (threadIdx.x + i * 256) * 4;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (j < hidden) {
+            if (FROM_BF16) {
+                v = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(in + row * hidden + j), f32x4);
+                *reinterpret_cast<f32x4*>(xr + j) = v;
+            } else {
+                v = *reinterpret_cast<const f32x4*>(xr + j);
+                for (int p = 0; p < planes; ++p)
+                    v += *reinterpret_cast<const f32x4*>(y + p * plane_stride + row * hidden + j);
+                if (planes > 0) *reinterpret_cast<f32x4*>(xr + j) = v;
+            }
         }
+        keep[i] = v;
         ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     }
-    float total = block_sum_256(ss, red);
-    float inv = 1.0f / sqrtf(total / (float)hidden + eps);
+    const float total = block_sum_256(ss, red);
+    const float inv = 1.0f / sqrtf(total / (float)hidden + eps);
     bf16_t* hr = h + row * ldh;
-    for (int j = threadIdx.x * 4; j < hidden; j += 1024) {
-        f32x4 v;
-        if (FROM_BF16) {
-            v = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(ir + j), f32x4);
-        } else {
-            v = *reinterpret_cast<const f32x4*>(xr + j);
-        }
-        f32x4 g = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(gamma + j), f32x4);
-        f32x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = v[e] * inv * g[e];
-        *reinterpret_cast<bf16x4*>(hr + j) = __builtin_convertvector(o, bf16x4);
+    for (int i = 0; i < MAXV; ++i) {
+        const int j = (threadIdx.x + i * 256) * 4;
+        if (j < hidden) {
+            const f32x4 g = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(gamma + j), f32x4);
+            f32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = keep[i][e] * inv * g[e];
+            *reinterpret_cast<bf16x4*>(hr + j) = __builtin_convertvector(o, bf16x4);
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void cast_out_kernel(const float* __restrict__ x, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(256) void cast_out_kernel(const float* __restrict__ x, const float* __restrict__ y,
+                                                        int planes, int64_t plane_stride, bf16_t* __restrict__ out,
                                                         float* __restrict__ out_f32, int64_t count4) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= count4) return;
     f32x4 v = reinterpret_cast<const f32x4*>(x)[i];
+    for (int p = 0; p < planes; ++p) v += reinterpret_cast<const f32x4*>(y + p * plane_stride)[i];
     reinterpret_cast<bf16x4*>(out)[i] = __builtin_convertvector(v, bf16x4);
     if (out_f32) reinterpret_cast<f32x4*>(out_f32)[i] = v;
 }
@@ -149,24 +159,39 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
 
 }  // namespace
 
+template <bool FROM_BF16>
+hipError_t launch_rmsnorm_any(const bf16_t* in, float* x, const float* y, int planes, int64_t plane_stride,
+                              const bf16_t* gamma, bf16_t* h, int64_t ldh, int rows, int hidden, float eps,
+                              hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    if (hidden % 4 != 0 || hidden > 16 * 1024) return hipErrorInvalidValue;
+    const int vecs = (int)ceil_div(hidden, 1024);
+#define GLLM_RMS(V) rmsnorm_kernel<FROM_BF16, V><<<rows, 256, 0, stream>>>(in, x, y, planes, plane_stride, gamma, h, ldh, hidden, eps)
+    if (vecs <= 1) GLLM_RMS(1);
+    else if (vecs <= 2) GLLM_RMS(2);
+    else if (vecs <= 4) GLLM_RMS(4);
+    else if (vecs <= 5) GLLM_RMS(5);
+    else if (vecs <= 8) GLLM_RMS(8);
+    else GLLM_RMS(16);
+#undef GLLM_RMS
+    return hipGetLastError();
+}
+
 hipError_t launch_rmsnorm_from_bf16(const bf16_t* in, float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh,
                                     int rows, int hidden, float eps, hipStream_t stream) {
-    if (rows <= 0) return hipSuccess;
-    rmsnorm_kernel<true><<<rows, 256, 0, stream>>>(in, x, gamma, h, ldh, hidden, eps);
-    return hipGetLastError();
+    return launch_rmsnorm_any<true>(in, x, nullptr, 0, 0, gamma, h, ldh, rows, hidden, eps, stream);
 }
 
-hipError_t launch_rmsnorm(const float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh, int rows, int hidden,
-                          float eps, hipStream_t stream) {
-    if (rows <= 0) return hipSuccess;
-    rmsnorm_kernel<false><<<rows, 256, 0, stream>>>(nullptr, const_cast<float*>(x), gamma, h, ldh, hidden, eps);
-    return hipGetLastError();
+hipError_t launch_add_rmsnorm(float* x, const float* y, int planes, int64_t plane_stride, const bf16_t* gamma,
+                              bf16_t* h, int64_t ldh, int rows, int hidden, float eps, hipStream_t stream) {
+    return launch_rmsnorm_any<false>(nullptr, x, y, planes, plane_stride, gamma, h, ldh, rows, hidden, eps, stream);
 }
 
-hipError_t launch_cast_out(const float* x, bf16_t* out, float* out_f32, int64_t count, hipStream_t stream) {
+hipError_t launch_add_cast_out(const float* x, const float* y, int planes, int64_t plane_stride, bf16_t* out,
+                               float* out_f32, int64_t count, hipStream_t stream) {
     if (count <= 0) return hipSuccess;
     int64_t c4 = count / 4;
-    cast_out_kernel<<<(unsigned)ceil_div(c4, 256), 256, 0, stream>>>(x, out, out_f32, c4);
+    cast_out_kernel<<<(unsigned)ceil_div(c4, 256), 256, 0, stream>>>(x, y, planes, plane_stride, out, out_f32, c4);
     return hipGetLastError();
 }
 

@@ -22,29 +22,31 @@ def padded_rows(bits, rows):
     return out
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (52, 512, 256), (300, 384, 192), (257, 1280, 704), (1024, 256, 2048)])
-def test_gemm_store_and_add(M, N, K):
-    print(f"gemm store/add M={M} N={N} K={K}", flush=True)
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (52, 512, 256), (300, 768, 192), (257, 1280, 704), (1024, 256, 2048)])
+def test_gemm_store_and_add(M, N, K, tile):
+    print(f"gemm store/add M={M} N={N} K={K} tile={tile}", flush=True)
     a = rand_bits(1, 1, (M, K), 1.0)
     w = rand_bits(1, 2, (N, K), 0.05)
     ref = oracle.linear(oracle.bf16_to_f64(a), w)
     Mp = (M + 255) // 256 * 256
     da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w)
     out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
-    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, tile)
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)
     scale = np.abs(ref).max()
     assert np.abs(got - ref).max() <= 2e-5 * scale + 1e-6
-    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, tile)
     torch.cuda.synchronize()
     got2 = out.cpu().numpy().astype(np.float64)
     assert np.abs(got2 - 2 * ref).max() <= 4e-5 * scale + 1e-6
 
 
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3])
 @pytest.mark.parametrize("M,I,K", [(52, 768, 256), (130, 128, 128), (300, 1408, 320)])
-def test_gemm_swiglu(M, I, K):
-    print(f"gemm swiglu M={M} I={I} K={K}", flush=True)
+def test_gemm_swiglu(M, I, K, tile):
+    print(f"gemm swiglu M={M} I={I} K={K} tile={tile}", flush=True)
     a = rand_bits(2, 1, (M, K), 1.0)
     wg = rand_bits(2, 2, (I, K), 0.08)
     wu = rand_bits(2, 3, (I, K), 0.08)
@@ -58,7 +60,7 @@ def test_gemm_swiglu(M, I, K):
         packed[64 * blk + 32: 64 * blk + 64] = wu[32 * blk: 32 * blk + 32]
     Mp = (M + 255) // 256 * 256
     out = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
-    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(packed), out, M, 2 * I, K, B.GEMM_SWIGLU_BF16)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(packed), out, M, 2 * I, K, B.GEMM_SWIGLU_BF16, tile)
     torch.cuda.synchronize()
     got = oracle.bf16_to_f64(bits_of(out))
     err = np.abs(got - ref)
