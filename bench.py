@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--config", default="llama3_8b_pp4")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-index", type=int, default=0, help="batch of the 70B-shaped series")
+    ap.add_argument("--layers", type=int, default=0, help="experiment: run only this many layers of the stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     args = ap.parse_args()
@@ -67,6 +68,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     shape = synth.SHAPES[args.config]
+    if args.layers > 0:
+        import dataclasses
+        shape = dataclasses.replace(shape, num_layers=args.layers)
     batch = synth.make_batch(args.config, args.seed, args.batch_index)
     T = batch.num_tokens
 
@@ -176,7 +180,7 @@ def main():
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.config, "layers": L, "tokens_per_batch": T,
+        "config": {"workload": args.config + (f"[first {args.layers} layers]" if args.layers > 0 else ""), "layers": L, "tokens_per_batch": T,
                    "prefill_tokens": int(batch.new_tokens[batch.new_tokens > 1].sum()),
                    "decode_seqs": int((batch.new_tokens == 1).sum()),
                    "mean_decode_context": float(np.mean(batch.cached_len[batch.new_tokens == 1])) if (batch.new_tokens == 1).any() else 0.0,

@@ -23,8 +23,10 @@ _lib = None
 def build(force: bool = True) -> str:
     """Compile stage_oracle.c with gcc (baseline x86-64 plus runtime-dispatched clones)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-ftree-vectorize", "-fopenmp", "-fPIC", "-shared", "-std=gnu11",
-               "-Wall", "-o", _SO, _SRC, "-lm"]
+        # -ffp-contract=off: no fused multiply-add, every operation rounds on its own, so results do not
+        # depend on the instruction set of the host or on the loop nest that produced them
+        cmd = ["gcc", "-O2", "-ftree-vectorize", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-std=gnu11", "-Wall", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
 

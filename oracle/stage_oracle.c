@@ -129,11 +129,15 @@ void oracle_rmsnorm(int64_t T, int H, const double *x, const uint16_t *gamma, do
 }
 
 /* ---------------------------------------------------------------- linear layer
- * y[t][n] = bias[n] + sum_k x[t][k] * W[n][k], the sum taken in ascending k.
- * The weight is first copied out as doubles with k as the slow index so that the innermost
- * loop runs over n; every y[t][n] still receives its terms in the same ascending-k order and
- * no output depends on T or on any other row.                                             */
+ * y[t][n] = bias[n] + sum_k x[t][k] * W[n][k], the sum taken in ascending k, every product and
+ * every addition rounded separately (the file is compiled with -ffp-contract=off), so each
+ * y[t][n] is the same sequence of IEEE operations whatever the loop nest around it: no output
+ * depends on T or on any other row.  Two loop nests compute exactly that sequence:
+ *   - few rows: for every n, walk W[n][:] once and form the dot product of each row with it;
+ *   - many rows: the weight is first copied out as doubles with k as the slow index so that the
+ *     innermost loop runs over n (which vectorises without reassociating any sum).            */
 #define ORACLE_NCHUNK 512
+#define ORACLE_FEW_ROWS 64
 
 __attribute__((target_clones("default", "arch=haswell", "arch=skylake-avx512")))
 static void axpy_rows(int K, int N, int n0, int n1, const double *xr, const double *wt, double *yr)
@@ -148,6 +152,19 @@ static void axpy_rows(int K, int N, int n0, int n1, const double *xr, const doub
 void oracle_linear(int64_t T, int K, int N, const double *x, const uint16_t *W,
                    const uint16_t *bias, double *y)
 {
+    if (T <= ORACLE_FEW_ROWS) {
+#pragma omp parallel for schedule(static)
+        for (int n = 0; n < N; ++n) {
+            const uint16_t *wr = W + (int64_t)n * K;
+            for (int64_t t = 0; t < T; ++t) {
+                const double *xr = x + t * K;
+                double acc = bias ? oracle_bf16_to_f64(bias[n]) : 0.0;
+                for (int k = 0; k < K; ++k) acc += xr[k] * oracle_bf16_to_f64(wr[k]);
+                y[t * N + n] = acc;
+            }
+        }
+        return;
+    }
     double *wt = (double *)malloc((size_t)K * (size_t)N * sizeof(double));
 #pragma omp parallel for schedule(static)
     for (int n = 0; n < N; ++n)

@@ -436,7 +436,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
             return n;
         };
         // largest partition that still yields a few workgroups per compute unit
-        const int64_t want = 2048;
+        const int64_t want = 6144;
         part = 256;
         for (int P = 16384; P >= 256; P >>= 1)
             if (items_for(P) * c.n_kv_heads >= want) { part = P; break; }

@@ -176,7 +176,7 @@ __device__ __forceinline__ void init_state(AttnState<D, NB>& st) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Decode: grid (items, kv heads), 4 waves.  The item's key partition is cut into four runs of
+// Decode: one workgroup of 4 waves per (item, kv head).  The item's key partition is cut into four runs of
 // 32-key blocks, one per wave; the waves' partial results are merged through LDS and written as
 // one partial (running max, sum, unnormalised output) per query head of the KV head.
 // ------------------------------------------------------------------------------------------
@@ -186,8 +186,11 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a, const
                                                                 float* __restrict__ part_ml) {
     __shared__ float lds_o[4][16][D + 4];
     __shared__ float lds_m[4][16], lds_l[4][16];
-    const DecodeItem it = items[blockIdx.x];
-    const int kvh = blockIdx.y;
+    // the KV heads of one item are neighbouring workgroups: they run at the same time and read
+    // neighbouring 4 KiB pieces of the same pages
+    const int item_idx = blockIdx.x / a.n_kv;
+    const int kvh = blockIdx.x % a.n_kv;
+    const DecodeItem it = items[item_idx];
     const int g = a.n_q / a.n_kv;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a, const
             for (int v = 0; v < 4; ++v) acc[v] += ov[v] * sc;
             ls += lds_l[w][j] * sc;
         }
-        const int64_t slot = ((int64_t)blockIdx.x * a.n_q + kvh * g + j);
+        const int64_t slot = ((int64_t)item_idx * a.n_q + kvh * g + j);
         *reinterpret_cast<f32x4*>(part_o + slot * D + e) = acc;
         if (e == 0) {
             part_ml[slot * 2] = ms;
@@ -331,7 +334,7 @@ __global__ __launch_bounds__(64) void prefill_attention_kernel(AttnArgs a, const
 hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
                                    float* part_ml, hipStream_t stream) {
     if (num_items <= 0) return hipSuccess;
-    dim3 grid(num_items, a.n_kv);
+    dim3 grid(num_items * a.n_kv);
     if (a.d == 128) decode_attention_kernel<128><<<grid, 256, 0, stream>>>(a, items, part_o, part_ml);
     else if (a.d == 64) decode_attention_kernel<64><<<grid, 256, 0, stream>>>(a, items, part_o, part_ml);
     else return hipErrorInvalidValue;

@@ -22,6 +22,8 @@
 // the tiles an XCD works on at one time share a few A row-panels and W row-panels in its L2.
 #include "common.h"
 
+#include <cmath>
+
 namespace {
 
 constexpr int BK = 64;
@@ -35,8 +37,7 @@ template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ W, int64_t ldw,
                                                                     void* __restrict__ out, int64_t ldc, int M,
-                                                                    int N, int K, int tiles_m, int tiles_n, int64_t split_stride,
-                                                                    int dbg) {
+                                                                    int N, int K, int tiles_m, int tiles_n, int64_t split_stride) {
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
@@ -82,21 +83,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     const uint32_t voff_w = (uint32_t)(lrow * ldw + lgrp * 8) * 2u;
     const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
     const char* w_tile = reinterpret_cast<const char*>(W + (int64_t)n0 * ldw);
+    static_assert((BM / 8) % NW == 0, "A and W load groups must not mix within one unrolled step");
     auto issue_loads = [&](int kt, int stage) {
-        if ((dbg & 1) && kt > 1) return;  // timing experiment: no global loads after the first two tiles
-        if (dbg & 2) kt = 0;              // timing experiment: always the same k-slice (all cache hits)
-        kt += kt_base;
         unsigned char* sbase = smem + stage * STAGE_BYTES;
+        const int64_t kbyte = (int64_t)(kt + kt_base) * (BK * 2);
 #pragma unroll
         for (int i = 0; i < GPW; ++i) {
-            const int g = wave + i * NW;  // wave-uniform
-            if (g < BM / 8) {
-                const char* src = a_tile + ((int64_t)(g * 8) * lda + (int64_t)kt * BK) * 2 + voff_a;
-                __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sbase + g * 1024), 16, 0, 0);
-            } else {
-                const char* src = w_tile + ((int64_t)(g * 8 - BM) * ldw + (int64_t)kt * BK) * 2 + voff_w;
-                __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sbase + g * 1024), 16, 0, 0);
-            }
+            const int g = wave + i * NW;  // wave-uniform; A groups come first
+            const char* src = (i * NW < BM / 8) ? a_tile + (int64_t)(g * 8) * lda * 2 + kbyte + voff_a
+                                                : w_tile + (int64_t)(g * 8 - BM) * ldw * 2 + kbyte + voff_w;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sbase + g * 1024), 16, 0, 0);
         }
     };
 
@@ -143,6 +139,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
         __builtin_amdgcn_sched_group_barrier(0x100, kReads - kPaired, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kPaired, 0);
     };
+    // the step after the barrier also issues the next tile's global loads: one per MFMA, so that the
+    // matrix cores keep running while the loads are handed to the memory pipeline
+    constexpr int kLoadsPerMfma = (GPW + kMfma - 1) / kMfma;
+    auto interleave_with_loads = [&]() {
+#pragma unroll
+        for (int r = 0; r < kMfma; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (r * kLoadsPerMfma < GPW) __builtin_amdgcn_sched_group_barrier(0x020, kLoadsPerMfma, 0);
+            if (r < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
 
     // Software pipeline.  Global: tile kt+1 is in flight while tile kt is multiplied.  LDS -> registers:
     // the fragments of k-step kk+1 are fetched while k-step kk is multiplied, also across the tile
@@ -154,7 +161,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     __syncthreads();
     if (KT > 1) issue_loads(1, 1);
     load_frags(0, 0, 0);
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = 0; kt < KT - 1; ++kt) {
         const int stage = kt & 1;
 #pragma unroll
         for (int kk = 0; kk < KK - 1; ++kk) {
@@ -162,16 +169,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
             mfmas(kk & 1);
             interleave();
         }
-        if (kt + 1 < KT) {
-            if (!(DBG & 2)) {
-                if (!(DBG & 4)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();  // tile kt+1 has landed everywhere; every wave holds its last fragments of tile kt
-            }
-            if (kt + 2 < KT) issue_loads(kt + 2, stage);
-            if (!(DBG & 1)) load_frags(stage ^ 1, 0, KK & 1);
+        if (!(DBG & 2)) {
+            if (!(DBG & 4)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();  // tile kt+1 has landed everywhere; every wave holds its last fragments of tile kt
+        }
+        // branch-free tail (one scheduling region): the loads of tile kt+2 (past the end: the last tile once
+        // more, into the stage nobody reads again), the first fragments of tile kt+1, the last MFMAs of tile kt
+        if (!(DBG & 16)) issue_loads(min(kt + 2, KT - 1), stage);
+        if (!(DBG & 1)) load_frags(stage ^ 1, 0, KK & 1);
+        mfmas((KK - 1) & 1);
+        interleave_with_loads();
+    }
+    {
+        const int stage = (KT - 1) & 1;
+#pragma unroll
+        for (int kk = 0; kk < KK - 1; ++kk) {
+            load_frags(stage, kk + 1, (kk + 1) & 1);
+            mfmas(kk & 1);
+            interleave();
         }
         mfmas((KK - 1) & 1);
-        if (kt + 1 < KT) interleave();
     }
 
     if (DBG & 8) {  // timing experiment: no epilogue (one store keeps the accumulators alive)
@@ -239,8 +256,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     }
 }
 
-int g_gemm_debug = 0;
-
 template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                        int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
@@ -256,7 +271,7 @@ hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         configured = true;
     }
     kern<<<dim3(tiles_m * tiles_n, splits), 64 * WGM * WGN, smem, stream>>>(a, lda, w, ldw, out, ldc, m, n, k, tiles_m,
-                                                                          tiles_n, split_stride, g_gemm_debug);
+                                                                          tiles_n, split_stride);
     return hipGetLastError();
 }
 
@@ -276,6 +291,7 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 12: return launch_tile<256, 256, 2, 2, MODE, 8>(GLLM_TILE_ARGS);
         case 13: return launch_tile<256, 256, 2, 2, MODE, 12>(GLLM_TILE_ARGS);
         case 14: return launch_tile<256, 256, 2, 2, MODE, 11>(GLLM_TILE_ARGS);
+        case 15: return launch_tile<256, 256, 2, 2, MODE, 16>(GLLM_TILE_ARGS);
         default: return hipErrorInvalidValue;
     }
 #undef GLLM_TILE_ARGS
@@ -283,15 +299,17 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
 
 }  // namespace
 
-// Tile shape for a problem: the 256x256 tile (8 waves) feeds the matrix cores best, but a launch
-// should offer every compute unit work; when the big tile yields too few workgroups the 128x128 tile
-// (two workgroups per compute unit) fills the chip better.
+// Tile shape for a problem.  The 256x256 tile (8 waves, one workgroup per compute unit) feeds the
+// matrix cores best (about 1.13 PFLOP/s measured when all 256 compute units have a tile) but its
+// workgroups run in rounds of 256; the 128x128 tile (two workgroups per compute unit, about
+// 1.0 PFLOP/s) fills the chip in half-rounds of 256.  Pick the larger estimated throughput.
 int gemm_pick_tile(int m, int n, int splits) {
     if (n % 256 != 0) return 0;
-    const int64_t big = ceil_div(m, 256) * (int64_t)(n / 256) * splits;
-    if (big >= 160) return 3;
-    const int64_t small = ceil_div(m, 128) * (int64_t)(n / 128) * splits;
-    return (small > big * 2 || big < 96) ? 0 : 3;
+    const double big = (double)(ceil_div(m, 256) * (int64_t)(n / 256) * splits);
+    const double small = (double)(ceil_div(m, 128) * (int64_t)(n / 128) * splits);
+    const double big_util = big / (std::ceil(big / 256.0) * 256.0);
+    const double small_util = small / (std::ceil(small / 256.0) * 256.0);
+    return 1.13 * big_util >= 1.0 * small_util ? 3 : 0;
 }
 
 // Split-K factor for a GEMM whose consumer can sum partial outputs: enough workgroups to give every
@@ -312,8 +330,6 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
     if (lda * 16 >= (int64_t)1 << 31 || ldw * 16 >= (int64_t)1 << 31) return hipErrorInvalidValue;
     if (splits < 1 || (k / BK) % splits != 0) return hipErrorInvalidValue;
     if (splits > 1 && mode != GEMM_STORE_F32) return hipErrorInvalidValue;
-    g_gemm_debug = tile >= 0 ? tile >> 4 : 0;  // bits 4.. of a forced tile id select timing experiments
-    if (tile >= 0) tile &= 15;
     if (tile < 0) tile = gemm_pick_tile(m, n, splits);
     switch (mode) {
         case GEMM_STORE_F32:

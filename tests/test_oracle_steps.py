@@ -362,3 +362,17 @@ def test_attention_ignores_positions_after_the_row_and_other_layers():
     np.testing.assert_array_equal(a, b)
     want = _brute_force_attention(q, oracle.bf16_to_f64(Kb)[:21], oracle.bf16_to_f64(Vb)[:21], 2, 1, 20)
     np.testing.assert_allclose(a, want, rtol=1e-12)
+
+
+def test_linear_few_rows_and_many_rows_paths_agree_bitwise():
+    """The two loop nests of the linear layer perform the same operations in the same order."""
+    rng = np.random.default_rng(16)
+    K, N = 96, 600
+    x = rng.standard_normal((70, K))
+    w = bits_of(rng.standard_normal((N, K)))
+    b = bits_of(rng.standard_normal(N))
+    many = oracle.linear(x, w, b)               # 70 rows: transposed-copy path
+    few = oracle.linear(x[:5], w, b)            # 5 rows: dot-product path
+    np.testing.assert_array_equal(few, many[:5])
+    one = oracle.linear(x[69:70], w, b)
+    np.testing.assert_array_equal(one[0], many[69])
