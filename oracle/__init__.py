@@ -35,7 +35,8 @@ class Config(C.Structure):
     _fields_ = [("num_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("intermediate", C.c_int32),
                 ("page_size", C.c_int32), ("has_qkv_bias", C.c_int32),
-                ("rms_eps", C.c_double), ("rope_theta", C.c_double)]
+                ("rms_eps", C.c_double), ("rope_theta", C.c_double),
+                ("round_operands", C.c_int32), ("reserved", C.c_int32)]
 
 
 _W_FIELDS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "norm1", "norm2", "bq", "bk", "bv")
@@ -63,11 +64,11 @@ def lib():
     return _lib
 
 
-def make_config(shape) -> Config:
+def make_config(shape, round_operands: bool = False) -> Config:
     """shape: any object with the StageShape attribute names."""
     return Config(shape.num_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                   shape.intermediate, shape.page_size, int(bool(shape.has_qkv_bias)),
-                  float(shape.rms_eps), float(shape.rope_theta))
+                  float(shape.rms_eps), float(shape.rope_theta), int(bool(round_operands)), 0)
 
 
 def _p(a: Optional[np.ndarray]):
@@ -202,12 +203,14 @@ def pool_index(shape, which: str, num_pages: int, layer: int, page: int, kvh: in
 
 
 def stage_forward(shape, layers: Sequence[Dict[str, np.ndarray]], new_tokens, cached_len, block_tables,
-                  num_pages: int, k_pool: np.ndarray, v_pool: np.ndarray, hidden_bits: np.ndarray):
+                  num_pages: int, k_pool: np.ndarray, v_pool: np.ndarray, hidden_bits: np.ndarray,
+                  round_operands: bool = False):
     """Runs the stage; k_pool / v_pool (uint16, flat) are updated in place.
 
+    round_operands selects the diagnostic reading (bf16 tensors in front of every matrix product).
     Returns (out_f64 [T,H], out_bf16_bits [T,H]).
     """
-    cfg = make_config(shape)
+    cfg = make_config(shape, round_operands)
     arr = (Layer * len(layers))(*[make_layer(w) for w in layers])
     nt, cl, bt = _i32(new_tokens), _i32(cached_len), _i32(block_tables)
     T = int(nt.sum())

@@ -46,6 +46,13 @@ typedef struct {
     int32_t num_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, page_size;
     int32_t has_qkv_bias;
     double rms_eps, rope_theta;
+    /* 0: the plain definition (the default everywhere).  1: diagnostic reading in which the tensors
+     * that feed matrix products -- normalised activations, rotated queries, attention output, SwiGLU
+     * output -- are rounded to bf16 where a bf16 model stores them (paper section 4.1: all models use
+     * the bfloat16 data type); everything else stays double.  It separates the rounding noise of
+     * bf16 operands from errors of any other kind. */
+    int32_t round_operands;
+    int32_t reserved;
 } oracle_config;
 
 /* bf16 matrices are row-major [out_features][in_features]; biases may be NULL */
@@ -82,6 +89,13 @@ uint16_t oracle_f64_to_bf16(double x)
 void oracle_f64_to_bf16_array(int64_t n, const double *x, uint16_t *out)
 {
     for (int64_t i = 0; i < n; ++i) out[i] = oracle_f64_to_bf16(x[i]);
+}
+
+/* x <- the bf16 value nearest to x (ties to even), kept as a double */
+static void round_through_bf16(int64_t n, double *x)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) x[i] = oracle_bf16_to_f64(oracle_f64_to_bf16(x[i]));
 }
 
 /* ---------------------------------------------------------------- pool addressing */
@@ -320,24 +334,29 @@ void oracle_layer_forward(const oracle_config *c, int layer, const oracle_layer 
 
     /* attention half: x += Wo . attention(rope(Wq h), pool) with h = rmsnorm(x) */
     oracle_rmsnorm(T, H, x, w->norm1, c->rms_eps, h);
+    if (c->round_operands) round_through_bf16(T * (int64_t)H, h);
     oracle_linear(T, H, QD, h, w->wq, c->has_qkv_bias ? w->bq : NULL, q);
     oracle_linear(T, H, KD, h, w->wk, c->has_qkv_bias ? w->bk : NULL, k);
     oracle_linear(T, H, KD, h, w->wv, c->has_qkv_bias ? w->bv : NULL, v);
     oracle_rope(T, c->n_q_heads, d, pos_of, c->rope_theta, q);
     oracle_rope(T, c->n_kv_heads, d, pos_of, c->rope_theta, k);
+    if (c->round_operands) round_through_bf16(T * (int64_t)QD, q);
     oracle_kv_write(c, layer, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages, k, v,
                     k_pool, v_pool);
     oracle_attention(c, layer, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages, q,
                      k_pool, v_pool, o);
+    if (c->round_operands) round_through_bf16(T * (int64_t)QD, o);
     oracle_linear(T, QD, H, o, w->wo, NULL, y);
     for (int64_t i = 0; i < T * H; ++i) x[i] += y[i];
     if (tap) memcpy(tap, x, (size_t)T * H * sizeof(double));
 
     /* MLP half: x += Wd . (silu(Wg h2) * (Wu h2)) with h2 = rmsnorm(x) */
     oracle_rmsnorm(T, H, x, w->norm2, c->rms_eps, h);
+    if (c->round_operands) round_through_bf16(T * (int64_t)H, h);
     oracle_linear(T, H, I, h, w->wgate, NULL, gt);
     oracle_linear(T, H, I, h, w->wup, NULL, up);
     oracle_swiglu(T * (int64_t)I, gt, up, gt);
+    if (c->round_operands) round_through_bf16(T * (int64_t)I, gt);
     oracle_linear(T, I, H, gt, w->wdown, NULL, y);
     for (int64_t i = 0; i < T * H; ++i) x[i] += y[i];
 

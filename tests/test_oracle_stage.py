@@ -227,3 +227,22 @@ def test_tiny_configuration_matches_stored_values():
                                   batch.num_blocks, kp, vp, x)
     for t, j, val in rows:
         assert out[int(t), int(j)] == pytest.approx(float(val), rel=1e-9, abs=1e-12)
+
+
+def test_operand_rounding_reading_is_close_to_plain_and_keeps_the_invariants(weights):
+    total, num_pages = 48, 4
+    bt = np.array([[3, 0, 2]], dtype=np.int32)
+    x = hidden_np(SHAPE, 12, total)
+    def go(seqs, xs, kp, vp, ro):
+        return oracle.stage_forward(SHAPE, weights, [n for n, _ in seqs], [c for _, c in seqs], bt, num_pages,
+                                    kp, vp, xs, round_operands=ro)[0]
+    plain = go([(total, 0)], x, *fresh_pools(SHAPE, num_pages), False)
+    kp0, vp0 = fresh_pools(SHAPE, num_pages)
+    rounded = go([(total, 0)], x, kp0, vp0, True)
+    rel = np.abs(rounded - plain).sum() / np.abs(plain).sum()
+    assert 1e-5 < rel < 1e-2                      # a rounding-sized perturbation, not a different function
+    kp, vp = fresh_pools(SHAPE, num_pages)
+    a = go([(30, 0)], x[:30], kp, vp, True)
+    b = go([(18, 30)], x[30:], kp, vp, True)
+    assert np.array_equal(np.concatenate([a, b]), rounded)      # chunked == unchunked in this reading too
+    assert np.array_equal(kp, kp0) and np.array_equal(vp, vp0)
