@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="experiment: run only this many layers of the stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run three plain 1 GiB device-to-device copies and exit (reference dispatches for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (no sharding or collectives); "
@@ -67,6 +70,14 @@ def main():
         sys.exit(3)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return
     shape = synth.SHAPES[args.config]
     if args.layers > 0:
         import dataclasses

@@ -103,10 +103,11 @@ hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, i
 hipError_t launch_decode_combine(const AttnArgs& a, const DecodeRow* rows, int num_rows, const float* part_o,
                                  const float* part_ml, hipStream_t stream);
 
-// Prefill chunks: one work item per 64 consecutive query rows of a chunk.
+// Prefill chunks: one work item per prefill_item_rows() consecutive query rows of a chunk.
+int prefill_item_rows(int n_q, int n_kv);
 struct PrefillItem {
     int32_t row0;      // first token row of the tile
-    int32_t n_rows;    // valid query rows in the tile (1..64)
+    int32_t n_rows;    // valid query rows in the tile (1 .. prefill_item_rows)
     int32_t pos0;      // position of the first query row
     int32_t bt_off;    // offset of the sequence's first page id in bt_flat
 };

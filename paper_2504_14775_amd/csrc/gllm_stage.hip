@@ -38,7 +38,6 @@ struct LayerBuffers {
 };
 
 constexpr int kStagingSlots = 4;
-constexpr int kPrefillTileRows = 64;
 constexpr int kMaxSplits = 4;
 
 struct MetaLayout {  // offsets in bytes inside the metadata block (host staging and device copy alike)
@@ -54,7 +53,7 @@ struct gllm_stage {
     // derived sizes
     int q_dim = 0, kv_dim = 0, n_qkv = 0, n_qkv_pad = 0, inter_pad = 0, hidden_pad_n = 0;
     int64_t m_pad = 0;
-    int max_items = 0, max_pre_items = 0;
+    int max_items = 0, max_pre_items = 0, pre_rows = 64;
     std::vector<LayerBuffers> layers;
     float* rope_cs = nullptr;  // device [max_position][d/2][2]
     // workspace
@@ -217,7 +216,8 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
     s->hidden_pad_n = (int)round_up(c.hidden, kGemmPadN);
     s->m_pad = round_up(c.max_tokens, kGemmPadM);
     s->max_items = 4 * c.max_seqs + 1024;
-    s->max_pre_items = c.max_tokens / kPrefillTileRows + c.max_seqs + 1;
+    s->pre_rows = prefill_item_rows(c.n_q_heads, c.n_kv_heads);
+    s->max_pre_items = c.max_tokens / s->pre_rows + c.max_seqs + 1;
     s->layers.resize(c.num_layers);
 
     auto bail = [&](hipError_t err, const char* what) {
@@ -452,7 +452,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     int64_t cnt_items = 0, cnt_pre = 0;
     for (int i = 0; i < S; ++i) {
         if (b->new_tokens[i] == 1) cnt_items += ceil_div((int64_t)b->cached_len[i] + 1, part);
-        else cnt_pre += ceil_div(b->new_tokens[i], kPrefillTileRows);
+        else cnt_pre += ceil_div(b->new_tokens[i], s->pre_rows);
     }
     if (cnt_items > s->max_items || cnt_pre > s->max_pre_items)
         return fail(s, GLLM_E_CAPACITY, "internal work list overflow");
@@ -491,8 +491,8 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
             for (int k0 = 0; k0 < len; k0 += part)
                 dec_items[n_items++] = DecodeItem{(int32_t)row, (int32_t)bt_off, k0, std::min(k0 + part, len)};
         } else {
-            for (int t0 = 0; t0 < n; t0 += kPrefillTileRows)
-                pre_items[n_pre++] = PrefillItem{(int32_t)(row + t0), std::min(kPrefillTileRows, n - t0), cl + t0,
+            for (int t0 = 0; t0 < n; t0 += s->pre_rows)
+                pre_items[n_pre++] = PrefillItem{(int32_t)(row + t0), std::min(s->pre_rows, n - t0), cl + t0,
                                                  (int32_t)bt_off};
         }
         bt_off += pages;

@@ -54,76 +54,105 @@ struct AttnState {
     float l[NB];
 };
 
-// One block of 32 keys starting at key index tb.
-//   limit[c]   : last key visible to this lane's column in group c (causal / partition limit)
-//   valid_end  : keys >= valid_end hold no data yet (their V bits are forced to zero)
+// Masks the V fragments of keys >= valid_end (slots that hold no data yet may contain any bit pattern,
+// also NaN, and 0 * NaN would poison the P.V product).  v[p][b] holds 4 keys of page p, dims block b.
+template <int D>
+__device__ __forceinline__ void mask_unwritten_v(u32x2 (&v)[2][D / 16], int tb, int valid_end, int lane) {
+    const int G = lane >> 4;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        int nv = valid_end - (tb + p * 16 + G * 4);
+        nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+        const uint32_t m0 = nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0x0000FFFFu : 0u);
+        const uint32_t m1 = nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0x0000FFFFu : 0u);
+#pragma unroll
+        for (int b = 0; b < D / 16; ++b) {
+            v[p][b][0] &= m0;
+            v[p][b][1] &= m1;
+        }
+    }
+}
+
+// One column group against one block of 32 keys starting at key index tb, in two phases so that callers
+// can fetch the V fragments only after the K fragments are dead.
+// Phase 1: scores (already multiplied by log2(e)/sqrt(d)) of this lane's 8 keys, masked.
+//   limit     : last key visible to this lane's column (causal / partition limit)
+//   need_mask : wave-uniform, false when the whole block is visible to every column of the group
+template <int D>
+__device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2][D / 32], const bf16x8 (&qf)[D / 32],
+                                            int tb, int limit, bool need_mask, float scale_log2, int lane) {
+    const int G = lane >> 4;
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[0][s]), qf[s], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[1][s]), qf[s], s1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        sc[v] = s0[v] * scale_log2;
+        sc[4 + v] = s1[v] * scale_log2;
+    }
+    if (need_mask) {
+        const int t0 = tb + G * 4;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (t0 + v > limit) sc[v] = kNegBig;
+            if (t0 + 16 + v > limit) sc[4 + v] = kNegBig;
+        }
+    }
+}
+
+// Phase 2: running-maximum softmax update, then O^T += V^T P^T.  The accumulators are rescaled only when
+// some column's maximum moved (wave-uniform test), which after the first blocks is rare.
+template <int D>
+__device__ __forceinline__ void update_group(f32x4 (&o)[D / 16], float& m, float& l, const float (&sc)[8],
+                                             const u32x2 (&vf)[2][D / 16]) {
+    float bm = sc[0];
+#pragma unroll
+    for (int v = 1; v < 8; ++v) bm = fmaxf(bm, sc[v]);
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    const float m_new = fmaxf(m, bm);
+    if (__any(m_new > m)) {
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        l *= alpha;
+#pragma unroll
+        for (int b = 0; b < D / 16; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[b][v] *= alpha;
+        m = m_new;
+    }
+    f32x8 p;
+    float psum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        p[v] = __builtin_amdgcn_exp2f(sc[v] - m);
+        psum += p[v];
+    }
+    l += psum;
+    const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b) {
+        const u32x4 vv = {vf[0][b][0], vf[0][b][1], vf[1][b][0], vf[1][b][1]};
+        o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, o[b], 0, 0, 0);
+    }
+}
+
+// One block of 32 keys for NB column groups, K/V fragments in registers.
+//   limit[c]   : last key visible to this lane's column in group c
+//   valid_end  : keys >= valid_end hold no data yet
 template <int D, int NB>
 __device__ __forceinline__ void attend_block(AttnState<D, NB>& st, KvFrag<D>& f, const bf16x8 (&qf)[NB][D / 32],
                                              int tb, const int (&limit)[NB], int min_limit, int valid_end,
                                              float scale_log2, int lane) {
-    const int G = lane >> 4;
-    if (tb + 32 > valid_end) {  // wave-uniform
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            int nv = valid_end - (tb + p * 16 + G * 4);
-            nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
-            uint32_t m0 = nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0x0000FFFFu : 0u);
-            uint32_t m1 = nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0x0000FFFFu : 0u);
-#pragma unroll
-            for (int b = 0; b < D / 16; ++b) {
-                f.v[p][b][0] &= m0;
-                f.v[p][b][1] &= m1;
-            }
-        }
-    }
-    const bool need_mask = tb + 31 > min_limit;  // wave-uniform
+    if (tb + 32 > valid_end) mask_unwritten_v<D>(f.v, tb, valid_end, lane);  // wave-uniform
+    const bool need_mask = tb + 31 > min_limit;                              // wave-uniform
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.k[0][s]), qf[c][s], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.k[1][s]), qf[c][s], s1, 0, 0, 0);
-        }
         float sc[8];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            sc[v] = s0[v] * scale_log2;
-            sc[4 + v] = s1[v] * scale_log2;
-        }
-        if (need_mask) {
-            const int t0 = tb + G * 4;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (t0 + v > limit[c]) sc[v] = kNegBig;
-                if (t0 + 16 + v > limit[c]) sc[4 + v] = kNegBig;
-            }
-        }
-        float bm = sc[0];
-#pragma unroll
-        for (int v = 1; v < 8; ++v) bm = fmaxf(bm, sc[v]);
-        bm = fmaxf(bm, __shfl_xor(bm, 16));
-        bm = fmaxf(bm, __shfl_xor(bm, 32));
-        const float m_new = fmaxf(st.m[c], bm);
-        const float alpha = __builtin_amdgcn_exp2f(st.m[c] - m_new);
-        st.m[c] = m_new;
-        f32x8 p;
-        float psum = 0.f;
-#pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            p[v] = __builtin_amdgcn_exp2f(sc[v] - m_new);
-            psum += p[v];
-        }
-        st.l[c] = st.l[c] * alpha + psum;
-        const bf16x8 pb = __builtin_convertvector(p, bf16x8);
-#pragma unroll
-        for (int b = 0; b < D / 16; ++b) {
-            f32x4 o = st.o[c][b];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] *= alpha;
-            u32x4 vv = {f.v[0][b][0], f.v[0][b][1], f.v[1][b][0], f.v[1][b][1]};
-            st.o[c][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, o, 0, 0, 0);
-        }
+        score_group<D>(sc, f.k, qf[c], tb, limit[c], need_mask, scale_log2, lane);
+        update_group<D>(st.o[c], st.m[c], st.l[c], sc, f.v);
     }
 }
 
@@ -181,7 +210,7 @@ __device__ __forceinline__ void init_state(AttnState<D, NB>& st) {
 // one partial (running max, sum, unnormalised output) per query head of the KV head.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
+__global__ __launch_bounds__(256, 2) void decode_attention_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
                                                                 float* __restrict__ part_o,
                                                                 float* __restrict__ part_ml) {
     __shared__ float lds_o[4][16][D + 4];
@@ -281,43 +310,113 @@ __global__ void decode_combine_kernel(AttnArgs a, const DecodeRow* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// Prefill: grid (items, query heads), one wave per workgroup.  An item is up to 16*NB consecutive
-// query rows of a chunk; the wave walks keys 0 .. position of its last valid row.
+// Prefill: one workgroup of 4 waves per (item, group of HW query heads of one KV head).  An item is up
+// to 128/HW consecutive query rows of a chunk, so the workgroup owns 8 column groups of 16 (2 per wave)
+// that all share the same K/V: every 32-key block is brought into LDS once (global_load_lds into a ring
+// of 4 stages, three blocks in flight while one is processed: a block is only ~0.5 us of work, far less
+// than the memory latency) and read by all 4 waves.
+// LDS holds the pages exactly as the pool does, so the fragment reads are the same contiguous patterns
+// as in the decode kernel.  Column group cb = 2*wave + c covers head (cb % HW) and query rows
+// 16*(cb / HW) .. +15 of the item.
 // ------------------------------------------------------------------------------------------
-template <int D, int NB>
-__global__ __launch_bounds__(64) void prefill_attention_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
-    const PrefillItem it = items[blockIdx.x];
-    const int hq = blockIdx.y;
-    const int g = a.n_q / a.n_kv;
-    const int kvh = hq / g;
-    const int lane = threadIdx.x;
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int D, int HW>
+__global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
+    constexpr int NB = 2;
+    constexpr int PAGE_BYTES = D * kPage * 2;  // one (page, head) of K or of V
+    constexpr int NS = 4;                      // LDS stages
+    constexpr int IPB = PAGE_BYTES / 1024;     // load instructions per wave and block
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NS][4][PAGE_BYTES];  // [stage][K0,K1,V0,V1]
+    const int groups = a.n_q / HW;
+    const PrefillItem it = items[blockIdx.x / groups];
+    const int head0 = (blockIdx.x % groups) * HW;
+    const int kvh = head0 / (a.n_q / a.n_kv);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 15, G = lane >> 4;
 
     bf16x8 qf[NB][D / 32];
-    int limit[NB];
+    int limit[NB], wave_min = 0x7FFFFFFF, wave_max = -1;
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
-        const int qi = min(c * 16 + r, it.n_rows - 1);  // rows past the tile repeat its last row (never stored)
+        const int cb = wave * NB + c, qb = cb / HW;
+        const int qi = min(qb * 16 + r, it.n_rows - 1);  // rows past the item repeat its last row (never stored)
         limit[c] = it.pos0 + qi;
-        const bf16_t* qrow = a.q + (int64_t)(it.row0 + qi) * a.ld_q + (int64_t)hq * D;
+        wave_min = min(wave_min, it.pos0 + min(qb * 16, it.n_rows - 1));
+        wave_max = max(wave_max, it.pos0 + min(qb * 16 + 15, it.n_rows - 1));
+        const bf16_t* qrow = a.q + (int64_t)(it.row0 + qi) * a.ld_q + (int64_t)(head0 + cb % HW) * D;
 #pragma unroll
         for (int s = 0; s < D / 32; ++s)
             qf[c][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + (s * 4 + G) * 8));
     }
     const int last_pos = it.pos0 + it.n_rows - 1;
+    const int nblk = last_pos / 32 + 1, last_page = last_pos / kPage;
+    const int32_t* bt = a.bt_flat + it.bt_off;
+    // wave w brings in piece w of a block: K page 0, K page 1, V page 0, V page 1 (4 x 1 KiB per page at d=128)
+    const bf16_t* pool = (wave < 2) ? a.k_pool : a.v_pool;
+    auto page_id = [&](int blk) -> int { return bt[min(blk * 2 + (wave & 1), last_page)]; };
+    auto issue_block = [&](int64_t page, int stage) {
+        const char* src = reinterpret_cast<const char*>(pool + (page * a.n_kv + kvh) * (int64_t)(D * kPage)) + lane * 16;
+#pragma unroll
+        for (int i = 0; i < IPB; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + i * 1024), (lptr_t)(&lds[stage][wave][i * 1024]), 16, 0, 0);
+    };
+
     AttnState<D, NB> st;
     init_state<D, NB>(st);
-    attend_range<D, NB>(st, qf, a.k_pool, a.v_pool, a.bt_flat + it.bt_off, 0, last_pos / 32 + 1, last_pos / kPage,
-                        limit, it.pos0, last_pos + 1, a.n_kv, kvh, a.scale_log2, lane);
+    // every wave always issues its piece (indices past the end re-read the last page into a stage nobody
+    // reads), so the count of outstanding loads is the same in every iteration
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) issue_block(page_id(i), i);
+    int pid_next = page_id(NS - 1);  // page of block blk + NS - 1, fetched one iteration ahead
+    for (int blk = 0; blk < nblk; ++blk) {
+        const int stage = blk % NS;
+        // blocks blk+1 .. blk+NS-2 may still be in flight
+        if (NS == 4 && IPB == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (NS == 4 && IPB == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // block blk has landed; nobody reads stage (blk-1) % NS any more
+        issue_block(pid_next, (blk + NS - 1) % NS);
+        pid_next = page_id(blk + NS);
+        const int tb = blk * 32;
+        if (tb <= wave_max) {  // wave-uniform: later blocks are invisible to all of this wave's rows
+            const bool need_mask = tb + 31 > wave_min;
+            float sc[NB][8];
+            {
+                u32x4 kf[2][D / 32];
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+#pragma unroll
+                    for (int s = 0; s < D / 32; ++s)
+                        kf[p][s] = *reinterpret_cast<const u32x4*>(&lds[stage][p][(s * 64 + lane) * 16]);
+#pragma unroll
+                for (int c = 0; c < NB; ++c)
+                    score_group<D>(sc[c], kf, qf[c], tb, limit[c], need_mask, a.scale_log2, lane);
+            }
+            u32x2 vf[2][D / 16];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int b = 0; b < D / 16; ++b)
+                    vf[p][b] = *reinterpret_cast<const u32x2*>(&lds[stage][2 + p][((16 * b + r) * kPage + 4 * G) * 2]);
+            if (tb + 32 > last_pos + 1) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
+#pragma unroll
+            for (int c = 0; c < NB; ++c) update_group<D>(st.o[c], st.m[c], st.l[c], sc[c], vf);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no LDS fill may outlive the workgroup
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
         float l = st.l[c];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         const float inv = 1.0f / l;
-        const int qi = c * 16 + r;
+        const int cb = wave * NB + c;
+        const int qi = (cb / HW) * 16 + r;
         if (qi < it.n_rows) {
-            bf16_t* orow = a.out + (int64_t)(it.row0 + qi) * a.ld_o + (int64_t)hq * D;
+            bf16_t* orow = a.out + (int64_t)(it.row0 + qi) * a.ld_o + (int64_t)(head0 + cb % HW) * D;
 #pragma unroll
             for (int b = 0; b < D / 16; ++b) {
                 f32x4 o = st.o[c][b];
@@ -351,11 +450,27 @@ hipError_t launch_decode_combine(const AttnArgs& a, const DecodeRow* rows, int n
     return hipGetLastError();
 }
 
+int prefill_heads_per_workgroup(int n_q, int n_kv) {
+    const int g = n_q / n_kv;
+    return (g == 1 || g == 2 || g == 4 || g == 8) ? g : 1;
+}
+
+int prefill_item_rows(int n_q, int n_kv) { return 128 / prefill_heads_per_workgroup(n_q, n_kv); }
+
 hipError_t launch_prefill_attention(const AttnArgs& a, const PrefillItem* items, int num_items, hipStream_t stream) {
     if (num_items <= 0) return hipSuccess;
-    dim3 grid(num_items, a.n_q);
-    if (a.d == 128) prefill_attention_kernel<128, 4><<<grid, 64, 0, stream>>>(a, items);
-    else if (a.d == 64) prefill_attention_kernel<64, 4><<<grid, 64, 0, stream>>>(a, items);
-    else return hipErrorInvalidValue;
+    const int hw = prefill_heads_per_workgroup(a.n_q, a.n_kv);
+    const dim3 grid(num_items * (a.n_q / hw));
+#define GLLM_PREFILL(D_, HW_) prefill_attention_kernel<D_, HW_><<<grid, 256, 0, stream>>>(a, items)
+    if (a.d == 128) {
+        if (hw == 8) GLLM_PREFILL(128, 8); else if (hw == 4) GLLM_PREFILL(128, 4);
+        else if (hw == 2) GLLM_PREFILL(128, 2); else GLLM_PREFILL(128, 1);
+    } else if (a.d == 64) {
+        if (hw == 8) GLLM_PREFILL(64, 8); else if (hw == 4) GLLM_PREFILL(64, 4);
+        else if (hw == 2) GLLM_PREFILL(64, 2); else GLLM_PREFILL(64, 1);
+    } else {
+        return hipErrorInvalidValue;
+    }
+#undef GLLM_PREFILL
     return hipGetLastError();
 }

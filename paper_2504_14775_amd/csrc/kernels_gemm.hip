@@ -28,7 +28,10 @@ namespace {
 
 constexpr int BK = 64;
 
-__device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
+// silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (1 ulp each; the result is rounded to bf16)
+__device__ __forceinline__ float silu(float z) {
+    return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -192,6 +195,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     }
 
     if (DBG & 8) {  // timing experiment: no epilogue (one store keeps the accumulators alive)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no LDS fill may outlive the workgroup
         float s0 = 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -302,14 +306,14 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
 // Tile shape for a problem.  The 256x256 tile (8 waves, one workgroup per compute unit) feeds the
 // matrix cores best (about 1.13 PFLOP/s measured when all 256 compute units have a tile) but its
 // workgroups run in rounds of 256; the 128x128 tile (two workgroups per compute unit, about
-// 1.0 PFLOP/s) fills the chip in half-rounds of 256.  Pick the larger estimated throughput.
+// 0.92 PFLOP/s) fills the chip in half-rounds of 256.  Pick the larger estimated throughput.
 int gemm_pick_tile(int m, int n, int splits) {
     if (n % 256 != 0) return 0;
     const double big = (double)(ceil_div(m, 256) * (int64_t)(n / 256) * splits);
     const double small = (double)(ceil_div(m, 128) * (int64_t)(n / 128) * splits);
     const double big_util = big / (std::ceil(big / 256.0) * 256.0);
     const double small_util = small / (std::ceil(small / 256.0) * 256.0);
-    return 1.13 * big_util >= 1.0 * small_util ? 3 : 0;
+    return 1.13 * big_util >= 0.92 * small_util ? 3 : 0;
 }
 
 // Split-K factor for a GEMM whose consumer can sum partial outputs: enough workgroups to give every

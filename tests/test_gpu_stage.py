@@ -251,3 +251,20 @@ def test_forward_rejects_malformed_batches_without_side_effects():
     assert e.value.status == -5
     assert status_of(nt, cl, bt) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n_q,n_kv,d", [(6, 2, 128), (4, 4, 64), (8, 2, 64), (8, 1, 128), (10, 2, 64), (2, 1, 128)])
+def test_head_group_shapes(n_q, n_kv, d):
+    """Every query-heads-per-KV-head case of the attention kernels (1, 2, 3, 4, 5, 8) at both head sizes, on a
+    batch whose chunks span several 32-key blocks, item boundaries and ragged tails."""
+    print(f"head grouping n_q={n_q} n_kv={n_kv} d={d}", flush=True)
+    shape = synth.StageShape("grp", 2, 256, n_q, n_kv, d, 384)
+    seqs = [(150, 37), (130, 0), (1, 99), (1, 0), (17, 200), (1, 511), (3, 30)]
+    batch = synth.build_batch(seqs, 9, spare_blocks=5)
+    w = layer_weights_np(shape, 9)
+    kp0, vp0 = pool_np(shape, 9, batch.num_blocks)
+    r = run_both(shape, w, batch, kp0, vp0, hidden_np(shape, 9, batch.num_tokens))
+    assert_output(f"grp{n_q}/{n_kv}/{d}", r, literal=False)
+    mk, mv = written_mask(shape, batch)
+    check_pool("K", r["gk"], kp0, r["kp"], shape.num_layers, mask=mk)
+    check_pool("V", r["gv"], vp0, r["vp"], shape.num_layers, mask=mv)
