@@ -14,10 +14,12 @@
 // coalesced loads:
 //   K page [d/8][16 slots][8]: k-step s of S^T reads the 1 KiB at (64 s + lane) * 16 bytes;
 //   V page [d][16 slots]:      dims 16b..16b+15 of P.V read 8 bytes at ((16b + r) * 16 + 4G) * 2.
-// Softmax is the running-maximum form in base 2 (scores are pre-multiplied by log2(e)/sqrt(d));
+// Softmax is the running-reference form in base 2 (exponent s*log2(e)/sqrt(d) - m, see update_group);
 // all reductions follow logical key order, so the result does not depend on which physical pages
 // hold the keys.
 #include "common.h"
+
+#include <type_traits>
 
 namespace {
 
@@ -75,12 +77,12 @@ __device__ __forceinline__ void mask_unwritten_v(u32x2 (&v)[2][D / 16], int tb, 
 
 // One column group against one block of 32 keys starting at key index tb, in two phases so that callers
 // can fetch the V fragments only after the K fragments are dead.
-// Phase 1: scores (already multiplied by log2(e)/sqrt(d)) of this lane's 8 keys, masked.
+// Phase 1: raw scores q.k of this lane's 8 keys (not yet scaled), masked keys set to a huge negative.
 //   limit     : last key visible to this lane's column (causal / partition limit)
 //   need_mask : wave-uniform, false when the whole block is visible to every column of the group
 template <int D>
 __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2][D / 32], const bf16x8 (&qf)[D / 32],
-                                            int tb, int limit, bool need_mask, float scale_log2, int lane) {
+                                            int tb, int limit, bool need_mask, int lane) {
     const int G = lane >> 4;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -90,8 +92,8 @@ __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2]
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        sc[v] = s0[v] * scale_log2;
-        sc[4 + v] = s1[v] * scale_log2;
+        sc[v] = s0[v];
+        sc[4 + v] = s1[v];
     }
     if (need_mask) {
         const int t0 = tb + G * 4;
@@ -103,39 +105,79 @@ __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2]
     }
 }
 
-// Phase 2: running-maximum softmax update, then O^T += V^T P^T.  The accumulators are rescaled only when
-// some column's maximum moved (wave-uniform test), which after the first blocks is rare.
-template <int D>
-__device__ __forceinline__ void update_group(f32x4 (&o)[D / 16], float& m, float& l, const float (&sc)[8],
-                                             const u32x2 (&vf)[2][D / 16]) {
-    float bm = sc[0];
+// Phase 2, for all NB column groups of a wave at once: softmax update in base 2 and O^T += V^T P^T.
+//
+// m is the reference exponent of a column (identical in the four lanes that share the column); p =
+// 2^(s*c - m) with c = log2(e)/sqrt(d).  Softmax does not care which reference is used as long as nothing
+// overflows, so the block's own maximum is NOT awaited: p is formed against the reference left by the
+// earlier blocks while the block maximum travels across the lanes (two LDS-crossbar permutes per group,
+// ~150 cycles each) under the exponentials and MFMAs; only afterwards, if it exceeded the reference, are m,
+// l and the accumulators moved to it.  The exact order (reduce, move, exponentiate) is taken when some lane
+// sees a score more than 64 above its reference -- always in a wave's first block, where the reference
+// is still the huge negative start value -- so p stays below 2^64 and sums of 2^13 of them stay finite.
+// The code is straight-line except for those two rare wave-uniform branches, and all groups advance
+// together, so the scheduler can overlap the groups' dependency chains.  DEFER = false gives the plain
+// exact order (reference moved before the exponentials whenever a lane's maximum exceeds it): the
+// memory-bound decode kernel, with one group per wave, gains nothing from deferring and saves registers.
+constexpr float kRefSlack = 64.0f;
+
+template <int D, int NB, bool DEFER, typename GetV>
+__device__ __forceinline__ void update_groups(AttnState<D, NB>& st, const float (&sc)[NB][8], float scale_log2,
+                                              GetV&& get_v) {
+    float lm[NB], bm[NB];
+    bool low = false;
 #pragma unroll
-    for (int v = 1; v < 8; ++v) bm = fmaxf(bm, sc[v]);
-    bm = fmaxf(bm, __shfl_xor(bm, 16));
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
-    const float m_new = fmaxf(m, bm);
-    if (__any(m_new > m)) {
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        l *= alpha;
+    for (int c = 0; c < NB; ++c) {
+        float x = sc[c][0];
 #pragma unroll
-        for (int b = 0; b < D / 16; ++b)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) o[b][v] *= alpha;
-        m = m_new;
+        for (int v = 1; v < 8; ++v) x = fmaxf(x, sc[c][v]);
+        lm[c] = x * scale_log2;
+        low |= DEFER ? lm[c] > st.m[c] + kRefSlack : lm[c] > st.m[c];
     }
-    f32x8 p;
-    float psum = 0.f;
 #pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        p[v] = __builtin_amdgcn_exp2f(sc[v] - m);
-        psum += p[v];
+    for (int c = 0; c < NB; ++c) bm[c] = fmaxf(lm[c], __shfl_xor(lm[c], 16));
+#pragma unroll
+    for (int c = 0; c < NB; ++c) bm[c] = fmaxf(bm[c], __shfl_xor(bm[c], 32));
+    auto move_references = [&]() {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            const float m_new = fmaxf(st.m[c], bm[c]);
+            const float alpha = __builtin_amdgcn_exp2f(st.m[c] - m_new);
+            st.l[c] *= alpha;
+#pragma unroll
+            for (int b = 0; b < D / 16; ++b)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) st.o[c][b][v] *= alpha;
+            st.m[c] = m_new;
+        }
+    };
+    if (__any(low)) move_references();  // exact order: waits for the block maxima
+    bf16x8 pb[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        f32x8 p;
+        float psum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            p[v] = __builtin_amdgcn_exp2f(fmaf(sc[c][v], scale_log2, -st.m[c]));
+            psum += p[v];
+        }
+        st.l[c] += psum;
+        pb[c] = __builtin_convertvector(p, bf16x8);
     }
-    l += psum;
-    const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+    const u32x2 (&vf)[2][D / 16] = get_v();
 #pragma unroll
     for (int b = 0; b < D / 16; ++b) {
         const u32x4 vv = {vf[0][b][0], vf[0][b][1], vf[1][b][0], vf[1][b][1]};
-        o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb, o[b], 0, 0, 0);
+#pragma unroll
+        for (int c = 0; c < NB; ++c)
+            st.o[c][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb[c], st.o[c][b], 0, 0, 0);
+    }
+    if (DEFER) {
+        bool moved = false;
+#pragma unroll
+        for (int c = 0; c < NB; ++c) moved |= bm[c] > st.m[c];
+        if (__any(moved)) move_references();  // deferred: the next block starts from the new references
     }
 }
 
@@ -148,12 +190,10 @@ __device__ __forceinline__ void attend_block(AttnState<D, NB>& st, KvFrag<D>& f,
                                              float scale_log2, int lane) {
     if (tb + 32 > valid_end) mask_unwritten_v<D>(f.v, tb, valid_end, lane);  // wave-uniform
     const bool need_mask = tb + 31 > min_limit;                              // wave-uniform
+    float sc[NB][8];
 #pragma unroll
-    for (int c = 0; c < NB; ++c) {
-        float sc[8];
-        score_group<D>(sc, f.k, qf[c], tb, limit[c], need_mask, scale_log2, lane);
-        update_group<D>(st.o[c], st.m[c], st.l[c], sc, f.v);
-    }
+    for (int c = 0; c < NB; ++c) score_group<D>(sc[c], f.k, qf[c], tb, limit[c], need_mask, lane);
+    update_groups<D, NB, false>(st, sc, scale_log2, [&]() -> const u32x2 (&)[2][D / 16] { return f.v; });
 }
 
 // Walks key blocks [blk_begin, blk_end) (units of 32 keys) of one sequence.  Page ids are fetched 64
@@ -366,13 +406,36 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, c
 
     AttnState<D, NB> st;
     init_state<D, NB>(st);
+    auto block_step = [&](int stage, int tb, auto masked) {
+        constexpr bool MASKED = decltype(masked)::value;
+        float sc[NB][8];
+        {
+            u32x4 kf[2][D / 32];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int s = 0; s < D / 32; ++s)
+                    kf[p][s] = *reinterpret_cast<const u32x4*>(&lds[stage][p][(s * 64 + lane) * 16]);
+#pragma unroll
+            for (int c = 0; c < NB; ++c) score_group<D>(sc[c], kf, qf[c], tb, limit[c], MASKED, lane);
+        }
+        u32x2 vf[2][D / 16];
+        update_groups<D, NB, true>(st, sc, a.scale_log2, [&]() -> const u32x2 (&)[2][D / 16] {
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int b = 0; b < D / 16; ++b)
+                    vf[p][b] = *reinterpret_cast<const u32x2*>(&lds[stage][2 + p][((16 * b + r) * kPage + 4 * G) * 2]);
+            if (MASKED) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
+            return vf;
+        });
+    };
     // every wave always issues its piece (indices past the end re-read the last page into a stage nobody
     // reads), so the count of outstanding loads is the same in every iteration
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i) issue_block(page_id(i), i);
     int pid_next = page_id(NS - 1);  // page of block blk + NS - 1, fetched one iteration ahead
-    for (int blk = 0; blk < nblk; ++blk) {
-        const int stage = blk % NS;
+    auto ring_advance = [&](int blk) {
         // blocks blk+1 .. blk+NS-2 may still be in flight
         if (NS == 4 && IPB == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else if (NS == 4 && IPB == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
@@ -380,31 +443,18 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, c
         __syncthreads();  // block blk has landed; nobody reads stage (blk-1) % NS any more
         issue_block(pid_next, (blk + NS - 1) % NS);
         pid_next = page_id(blk + NS);
-        const int tb = blk * 32;
-        if (tb <= wave_max) {  // wave-uniform: later blocks are invisible to all of this wave's rows
-            const bool need_mask = tb + 31 > wave_min;
-            float sc[NB][8];
-            {
-                u32x4 kf[2][D / 32];
-#pragma unroll
-                for (int p = 0; p < 2; ++p)
-#pragma unroll
-                    for (int s = 0; s < D / 32; ++s)
-                        kf[p][s] = *reinterpret_cast<const u32x4*>(&lds[stage][p][(s * 64 + lane) * 16]);
-#pragma unroll
-                for (int c = 0; c < NB; ++c)
-                    score_group<D>(sc[c], kf, qf[c], tb, limit[c], need_mask, a.scale_log2, lane);
-            }
-            u32x2 vf[2][D / 16];
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int b = 0; b < D / 16; ++b)
-                    vf[p][b] = *reinterpret_cast<const u32x2*>(&lds[stage][2 + p][((16 * b + r) * kPage + 4 * G) * 2]);
-            if (tb + 32 > last_pos + 1) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
-#pragma unroll
-            for (int c = 0; c < NB; ++c) update_group<D>(st.o[c], st.m[c], st.l[c], sc[c], vf);
-        }
+    };
+    // Two loops with one barrier per block each (every wave passes nblk barriers in total): first the
+    // blocks wholly visible to every row of this wave -- no masks at all, the common case -- then the
+    // blocks at the causal edge / the end of the written keys (masked) and the wholly invisible ones (skipped).
+    const int n_full = min((wave_min + 1) / 32, nblk);
+    for (int blk = 0; blk < n_full; ++blk) {
+        ring_advance(blk);
+        block_step(blk % NS, blk * 32, std::false_type{});
+    }
+    for (int blk = n_full; blk < nblk; ++blk) {
+        ring_advance(blk);
+        if (blk * 32 <= wave_max) block_step(blk % NS, blk * 32, std::true_type{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no LDS fill may outlive the workgroup
 #pragma unroll
