@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-index", type=int, default=0, help="batch of the 70B-shaped series")
     ap.add_argument("--layers", type=int, default=0, help="experiment: run only this many layers of the stage")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="experiment: gllm_stage_set_option(NAME, VALUE) before running")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -86,6 +88,9 @@ def main():
     T = batch.num_tokens
 
     stage = binding.stage_for_batches(shape, [batch], device=dev)
+    for opt in args.option:
+        k, v = opt.split("=")
+        stage.set_option(k, int(v))
     host_weights = []          # kept only if the oracle will be timed
     for l in range(shape.num_layers):
         w = synth.make_layer_weights(shape, args.seed, l, device=dev)

@@ -135,6 +135,15 @@ gllm_status gllm_stage_bind_kv_pool(gllm_stage* stage, void* k_pool /*DEVICE*/, 
  * (sequence, logical page) pairs that receive new tokens name the same physical page. */
 gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);
 
+/* Tuning knobs (defaults are chosen for MI355X).  Known names:
+ *   "decode_min_workgroups" (default 6144): the keys of decode rows are cut into equal partitions (256 ..
+ *   16384 keys, powers of two) until partitions x KV heads reaches this many workgroups.
+ *   "overlap_attention" (default 1): prefill attention of a layer runs on an internal side stream next to
+ *   decode attention (forked from and joined back into the caller's stream with events); 0 keeps every
+ *   kernel on the caller's stream.  Per-kernel profiling always uses the single-stream order.
+ * Unknown names give GLLM_E_INVALID. */
+gllm_status gllm_stage_set_option(gllm_stage* stage, const char* name /*HOST*/, int64_t value);
+
 /* Runs all layers of the stage on the batch.
  *   hidden_in       DEVICE bf16 [T][hidden]   (T = sum of new_tokens)
  *   hidden_out      DEVICE bf16 [T][hidden]   residual stream after the last layer, RNE to bf16
@@ -162,7 +171,9 @@ const char* gllm_profile_class_name(int32_t i);
  * 1 add into fp32 out[m][ldc]; 2 SwiGLU: columns come in groups of 64 = 32 gate + 32 up
  * outputs, out is bf16 [m][ldc] with n/2 columns, out = silu(gate) * up.
  * tile: -1 lets the library choose the workgroup tile; 0 = 128x128, 1 = 256x128, 2 = 256x256
- * (4 wavefronts), 3 = 256x256 (8 wavefronts); a forced tile must divide n (GLLM_E_UNSUPPORTED otherwise). */
+ * (4 wavefronts), 3 = 256x256 (8 wavefronts), 4 = 256x256 tiles for whole rounds of the compute units plus
+ * 256x128 tiles for the remainder (only for shapes with such a remainder); a forced tile that does not fit
+ * the shape gives GLLM_E_UNSUPPORTED. */
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
                               int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream);
 

@@ -23,7 +23,7 @@ GEMM_STORE_F32, GEMM_ADD_F32, GEMM_SWIGLU_BF16 = 0, 1, 2
 EXPORTS = [
     "gllm_stage_create", "gllm_stage_destroy", "gllm_last_error", "gllm_status_name",
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
-    "gllm_stage_bind_kv_pool", "gllm_stage_set_alias_check", "gllm_stage_forward",
+    "gllm_stage_bind_kv_pool", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
     "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
 ]
@@ -91,6 +91,8 @@ def load_library():
     lib.gllm_stage_bind_kv_pool.argtypes = [vp, vp, vp, i64]
     lib.gllm_stage_set_alias_check.restype = i32
     lib.gllm_stage_set_alias_check.argtypes = [vp, i32]
+    lib.gllm_stage_set_option.restype = i32
+    lib.gllm_stage_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.gllm_stage_forward.restype = i32
     lib.gllm_stage_forward.argtypes = [vp, C.POINTER(gllm_batch), vp, vp, vp, vp]
     lib.gllm_stage_set_profiling.restype = i32
@@ -177,6 +179,9 @@ class Stage:
 
     def set_alias_check(self, on: bool) -> None:
         self._check(self.lib.gllm_stage_set_alias_check(self.handle, int(on)))
+
+    def set_option(self, name: str, value: int) -> None:
+        self._check(self.lib.gllm_stage_set_option(self.handle, name.encode(), int(value)))
 
     def forward(self, new_tokens, cached_len, block_tables, hidden_in, hidden_out, hidden_out_f32=None,
                 stream=None) -> None:

@@ -78,7 +78,13 @@ struct gllm_stage {
     hipEvent_t staging_ev[kStagingSlots] = {};
     bool staging_used[kStagingSlots] = {};
     int next_slot = 0;
+    // prefill attention runs on a side stream, concurrently with decode attention (one is bound by the matrix
+    // cores and latency, the other by HBM); fork/join events order it inside the caller's stream
+    hipStream_t side = nullptr;
+    hipEvent_t fork_ev[8] = {}, join_ev[8] = {};
+    bool overlap_attention = true;
     bool alias_check = true;
+    int64_t decode_min_workgroups = 6144;  // partition the keys of decode rows until at least this many workgroups exist
     // profiling
     bool profiling = false;
     struct Span { int cls; hipEvent_t a, b; };
@@ -273,6 +279,11 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
                 return bail(e, "hipEventCreate");
         }
     }
+    if ((e = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking)) != hipSuccess) return bail(e, "hipStreamCreate");
+    for (int i = 0; i < 8; ++i) {
+        if ((e = hipEventCreateWithFlags(&s->fork_ev[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+        if ((e = hipEventCreateWithFlags(&s->join_ev[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+    }
     s->ws_bytes = workspace_layout(s, nullptr);
     *out = s;
     return GLLM_OK;
@@ -291,6 +302,11 @@ void gllm_stage_destroy(gllm_stage* s) {
         if (s->staging[i]) (void)hipHostFree(s->staging[i]);
         if (s->staging_ev[i]) (void)hipEventDestroy(s->staging_ev[i]);
     }
+    for (int i = 0; i < 8; ++i) {
+        if (s->fork_ev[i]) (void)hipEventDestroy(s->fork_ev[i]);
+        if (s->join_ev[i]) (void)hipEventDestroy(s->join_ev[i]);
+    }
+    if (s->side) (void)hipStreamDestroy(s->side);
     for (auto& sp : s->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (auto ev : s->ev_pool) (void)hipEventDestroy(ev);
     delete s;
@@ -349,6 +365,20 @@ gllm_status gllm_stage_set_alias_check(gllm_stage* s, int32_t on) {
     if (!s) return GLLM_E_INVALID;
     s->alias_check = on != 0;
     return GLLM_OK;
+}
+
+gllm_status gllm_stage_set_option(gllm_stage* s, const char* name, int64_t value) {
+    if (!s || !name) return GLLM_E_INVALID;
+    if (std::strcmp(name, "overlap_attention") == 0) {
+        s->overlap_attention = value != 0;
+        return GLLM_OK;
+    }
+    if (std::strcmp(name, "decode_min_workgroups") == 0) {
+        if (value < 1) return fail(s, GLLM_E_INVALID, "decode_min_workgroups must be positive");
+        s->decode_min_workgroups = value;
+        return GLLM_OK;
+    }
+    return fail(s, GLLM_E_INVALID, std::string("unknown option: ") + name);
 }
 
 gllm_status gllm_stage_set_profiling(gllm_stage* s, int32_t on) {
@@ -436,7 +466,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
             return n;
         };
         // largest partition that still yields a few workgroups per compute unit
-        const int64_t want = 6144;
+        const int64_t want = s->decode_min_workgroups;
         part = 256;
         for (int P = 16384; P >= 256; P >>= 1)
             if (items_for(P) * c.n_kv_heads >= want) { part = P; break; }
@@ -545,9 +575,18 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         aa.bt_flat = d_bt; aa.out = s->attn; aa.ld_o = s->q_dim;
         aa.n_q = c.n_q_heads; aa.n_kv = c.n_kv_heads; aa.d = d;
         aa.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)d));
+        // both attention kernels read q and the pool and write disjoint rows of attn
+        const bool fork = n_pre > 0 && n_items > 0 && s->overlap_attention && !s->profiling;
         if (n_pre > 0) {
-            ProfScope ps(s, st, PC_ATTN_PREFILL);
-            HIP_TRY(s, launch_prefill_attention(aa, d_pre, n_pre, st));
+            hipStream_t ps_stream = st;
+            if (fork) {
+                HIP_TRY(s, hipEventRecord(s->fork_ev[l & 7], st));
+                HIP_TRY(s, hipStreamWaitEvent(s->side, s->fork_ev[l & 7], 0));
+                ps_stream = s->side;
+            }
+            ProfScope ps(s, ps_stream, PC_ATTN_PREFILL);
+            HIP_TRY(s, launch_prefill_attention(aa, d_pre, n_pre, ps_stream));
+            if (fork) HIP_TRY(s, hipEventRecord(s->join_ev[l & 7], s->side));
         }
         if (n_items > 0) {
             {
@@ -557,6 +596,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
             ProfScope ps(s, st, PC_ATTN_MERGE);
             HIP_TRY(s, launch_decode_combine(aa, d_rows, n_rows, s->part_o, s->part_ml, st));
         }
+        if (fork) HIP_TRY(s, hipStreamWaitEvent(st, s->join_ev[l & 7], 0));
         {
             // the projection writes split_o partial products; the next RMSNorm adds them to the residual stream
             ProfScope ps(s, st, PC_GEMM_O);

@@ -36,11 +36,13 @@ __device__ __forceinline__ float silu(float z) {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
+// The work of one workgroup: output tile number `wg_linear` of a tiles_m x tiles_n grid of BM x BN tiles
+// whose first column is n_base.
 template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                                    const bf16_t* __restrict__ W, int64_t ldw,
-                                                                    void* __restrict__ out, int64_t ldc, int M,
-                                                                    int N, int K, int tiles_m, int tiles_n, int64_t split_stride) {
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
+                                          int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
+                                          int tiles_m, int tiles_n, int n_base, int wg_linear,
+                                          int64_t split_stride) {
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
 
     // ---- tile assignment (XCD aware) ----
     const int num_tiles = tiles_m * tiles_n;
-    int wg = blockIdx.x;
+    int wg = wg_linear;
     {
         // XCD x receives workgroups x, x+8, ...: q of them, one more for x < rem
         const int q = num_tiles >> 3, rem = num_tiles & 7;
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     const int in_band = wg - band * BAND * tiles_m;
     const int tile_m = in_band / band_cols;
     const int tile_n = band * BAND + in_band % band_cols;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = tile_m * BM, n0 = n_base + tile_n * BN;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -261,6 +263,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
 }
 
 template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                    const bf16_t* __restrict__ W, int64_t ldw,
+                                                                    void* __restrict__ out, int64_t ldc, int M,
+                                                                    int K, int tiles_m, int tiles_n,
+                                                                    int64_t split_stride) {
+    gemm_tile<BM, BN, WGM, WGN, MODE, DBG>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, blockIdx.x,
+                                           split_stride);
+}
+
+// Two tile shapes in one launch: the first big_tiles workgroups cover columns [0, n_split) with 256x256
+// tiles (whole rounds of the 256 compute units), the rest cover [n_split, N) with 256x128 tiles, so that
+// the last, partial round still gives every compute unit a (half-size) tile.  8 waves either way.
+template <int MODE>
+__global__ __launch_bounds__(512) void gemm_bf16_mixed_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                               const bf16_t* __restrict__ W, int64_t ldw,
+                                                               void* __restrict__ out, int64_t ldc, int M, int K,
+                                                               int tiles_m, int big_cols, int small_cols) {
+    const int big_tiles = tiles_m * big_cols;
+    if ((int)blockIdx.x < big_tiles)
+        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, big_cols, 0, blockIdx.x, 0);
+    else
+        gemm_tile<256, 128, 4, 2, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, small_cols, big_cols * 256,
+                                        blockIdx.x - big_tiles, 0);
+}
+
+template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                        int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
     if (n % BN != 0) return hipErrorInvalidValue;
@@ -274,7 +302,7 @@ hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<dim3(tiles_m * tiles_n, splits), 64 * WGM * WGN, smem, stream>>>(a, lda, w, ldw, out, ldc, m, n, k, tiles_m,
+    kern<<<dim3(tiles_m * tiles_n, splits), 64 * WGM * WGN, smem, stream>>>(a, lda, w, ldw, out, ldc, m, k, tiles_m,
                                                                           tiles_n, split_stride);
     return hipGetLastError();
 }
@@ -301,7 +329,37 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
 #undef GLLM_TILE_ARGS
 }
 
+// Mixed launch (see gemm_bf16_mixed_kernel); rem_cols 256-wide tile columns are turned into 2*rem_cols
+// 128-wide ones.
+template <int MODE>
+hipError_t launch_mixed(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
+                        int n, int k, int rem_cols, hipStream_t stream) {
+    const int tiles_m = (int)ceil_div(m, 256), big_cols = n / 256 - rem_cols, small_cols = 2 * rem_cols;
+    const size_t smem = 2 * (256 + 256) * BK * sizeof(bf16_t);
+    auto kern = gemm_bf16_mixed_kernel<MODE>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    kern<<<tiles_m * (big_cols + small_cols), 512, smem, stream>>>(a, lda, w, ldw, out, ldc, m, k, tiles_m, big_cols,
+                                                                   small_cols);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// Number of 256-wide tile columns to split in two for a mixed launch, or 0 when a plain launch is as good:
+// worth it when the last round of 256x256 tiles would occupy at most half of the compute units.
+int gemm_mixed_rem_cols(int m, int n) {
+    if (n % 256 != 0) return 0;
+    const int tiles_m = (int)ceil_div(m, 256), cols = n / 256;
+    const int tiles = tiles_m * cols, rem = tiles % 256;
+    if (tiles < 256 || rem == 0 || rem > 128 || rem % tiles_m != 0) return 0;
+    return rem / tiles_m;
+}
 
 // Tile shape for a problem.  The 256x256 tile (8 waves, one workgroup per compute unit) feeds the
 // matrix cores best (about 1.13 PFLOP/s measured when all 256 compute units have a tile) but its
@@ -334,6 +392,20 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
     if (lda * 16 >= (int64_t)1 << 31 || ldw * 16 >= (int64_t)1 << 31) return hipErrorInvalidValue;
     if (splits < 1 || (k / BK) % splits != 0) return hipErrorInvalidValue;
     if (splits > 1 && mode != GEMM_STORE_F32) return hipErrorInvalidValue;
+    if (tile < 0 && splits == 1) {
+        const int rem_cols = gemm_mixed_rem_cols(m, n);
+        if (rem_cols > 0) tile = 4;
+    }
+    if (tile == 4) {  // mixed 256x256 / 256x128 launch
+        const int rem_cols = gemm_mixed_rem_cols(m, n);
+        if (rem_cols == 0 || splits != 1) return hipErrorInvalidValue;
+        switch (mode) {
+            case GEMM_STORE_F32: return launch_mixed<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream);
+            case GEMM_ADD_F32: return launch_mixed<GEMM_ADD_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream);
+            case GEMM_SWIGLU_BF16: return launch_mixed<GEMM_SWIGLU_BF16>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream);
+            default: return hipErrorInvalidValue;
+        }
+    }
     if (tile < 0) tile = gemm_pick_tile(m, n, splits);
     switch (mode) {
         case GEMM_STORE_F32:

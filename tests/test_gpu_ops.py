@@ -78,3 +78,36 @@ def test_rmsnorm(T, H):
     torch.cuda.synchronize()
     got = oracle.bf16_to_f64(bits_of(h))
     assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 * 1.01 + 1e-6)
+
+
+@pytest.mark.parametrize("tile", [-1, 4])
+@pytest.mark.parametrize("mode", ["store", "swiglu"])
+def test_gemm_mixed_tile_launch(mode, tile):
+    """A grid whose last round of 256x256 tiles would be partial: 320 tiles -> 256 big + 128 half-width tiles."""
+    M, N, K = 500, 40960, 128
+    print(f"gemm mixed launch mode={mode} tile={tile}", flush=True)
+    a = rand_bits(5, 1, (M, K), 1.0)
+    x = oracle.bf16_to_f64(a)
+    Mp = (M + 255) // 256 * 256
+    if mode == "store":
+        w = rand_bits(5, 2, (N, K), 0.05)
+        ref = oracle.linear(x, w)
+        out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w), out, M, N, K, B.GEMM_STORE_F32, tile)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-6
+    else:
+        I = N // 2
+        wg = rand_bits(5, 3, (I, K), 0.08)
+        wu = rand_bits(5, 4, (I, K), 0.08)
+        ref = oracle.swiglu(oracle.linear(x, wg), oracle.linear(x, wu))
+        packed = np.zeros((N, K), dtype=np.uint16)
+        pk = packed.reshape(I // 32, 2, 32, K)
+        pk[:, 0] = wg.reshape(I // 32, 32, K)
+        pk[:, 1] = wu.reshape(I // 32, 32, K)
+        out = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
+        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(packed), out, M, N, K, B.GEMM_SWIGLU_BF16, tile)
+        torch.cuda.synchronize()
+        got = oracle.bf16_to_f64(bits_of(out))
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-4)
