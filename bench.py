@@ -26,6 +26,13 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by a
+# plain 1 GiB copy (profiles/stage_llama3_8b_pp4_hbm_traffic.txt): mean over the GEMM launches of a step,
+# and the decode attention kernel.  Measured offline (counters cannot be read from inside the process).
+MEASURED_TRAFFIC_BYTES = {
+    "llama3_8b_pp4": {"gemm": 497.8e6, "decode_attention": 2467.0e6 + 21.5e6},
+}
+
 
 def prefill_attn_flops(shape, batch):
     f = 0
@@ -152,7 +159,9 @@ def main():
         achieved = gemm_flop_step / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
         roofline = {"kernel": "gemm_bf16_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "launches_per_step": gemm_launches,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get("gemm") if args.layers == 0 else None,
+                    "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated; includes Infinity Cache hits)",
+                    "launches_per_step": gemm_launches,
                     "avg_launch_ms": round(gemm_ms / max(gemm_launches, 1), 5),
                     "flop_per_launch": gemm_flop_step / max(gemm_launches, 1)}
         H, I = shape.hidden, shape.intermediate
@@ -165,7 +174,8 @@ def main():
             gbs = kvb * L / (per_step["attn_decode"] * 1e-3) / 1e9
             extra["roofline_decode_attention"] = {
                 "kernel": "decode_attention_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
-                "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get("decode_attention") if args.layers == 0 else None,
                 "avg_launch_ms": round(per_step["attn_decode"] / L, 5), "bytes_per_launch": kvb}
         pf = prefill_attn_flops(shape, batch)
         if per_step.get("attn_prefill", 0) > 0:
@@ -176,6 +186,20 @@ def main():
                 "avg_launch_ms": round(per_step["attn_prefill"] / L, 5), "flop_per_launch": pf}
         extra["kernel_ms_per_step"] = {k: round(v, 4) for k, v in per_step.items()}
         extra["kernel_ms_sum"] = round(sum(per_step.values()), 4)
+
+    # ---- what this GPU sustains on a bare MFMA loop (bf16 operands like the GEMMs') and a bare streaming read ----
+    sink = torch.randn(8192, device=dev).to(torch.bfloat16)
+    probe = torch.empty(4 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    binding.gllm_op_peak_mfma(sink, 1024, 500); binding.gllm_op_peak_read(probe, probe.numel(), sink, 16384)
+    ev[0].record(); binding.gllm_op_peak_mfma(sink, 1024, 4000); ev[1].record()
+    ev[2].record(); binding.gllm_op_peak_read(probe, probe.numel(), sink, 16384); ev[3].record()
+    torch.cuda.synchronize()
+    extra["ceiling_probes"] = {
+        "mfma_loop_tflops": round(1024 * 4 * 4000 * 16 * 2 * 32 * 32 * 16 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12, 1),
+        "stream_read_gbs": round(probe.numel() / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9, 1),
+        "note": "bare 32x32x16 bf16 MFMA loop on random operands / bare 16-byte streaming read of 4 GiB, same box"}
+    del probe
 
     # ---- CPU oracle on a bounded sample of the same batch ----
     cpu = None
