@@ -214,7 +214,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     constexpr int C = (MODE == GEMM_SWIGLU_BF16) ? WTN / 2 : WTN;  // result columns of a wave slab
     constexpr int CS = C + 8;                                       // padded row stride (floats)
     constexpr int LPR = C / 4;                                      // lanes per row on the way out
-    constexpr int RPI = 64 / LPR;                                   // rows per read instruction
+    constexpr int RPI = 64 / LPR;                                   // rows per read instruction (lanes >= RPI*LPR idle)
+    static_assert(32 % RPI == 0, "a slab must be a whole number of read instructions");
     static_assert(NW * 32 * CS * 4 <= 2 * STAGE_BYTES, "epilogue slab must fit in the tile buffers");
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * CS);
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
@@ -242,6 +243,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
 #pragma unroll
         for (int r = 0; r < 32; r += RPI) {
             const int m = mrow0 + r + orow;
+            if (RPI * LPR < 64 && lane >= RPI * LPR) continue;
             const f32x4 val = *reinterpret_cast<const f32x4*>(slab + (r + orow) * CS + ocol);
             if (m < M) {
                 if (MODE == GEMM_SWIGLU_BF16) {
@@ -316,6 +318,9 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 1: return launch_tile<256, 128, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 2: return launch_tile<256, 256, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
+        case 5:
+            if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 2, 2, MODE>(GLLM_TILE_ARGS);
+            else return hipErrorInvalidValue;
         case 8: return launch_tile<256, 256, 2, 2, MODE, 1>(GLLM_TILE_ARGS);
         case 9: return launch_tile<256, 256, 2, 2, MODE, 2>(GLLM_TILE_ARGS);
         case 10: return launch_tile<256, 256, 2, 2, MODE, 3>(GLLM_TILE_ARGS);
@@ -365,13 +370,20 @@ int gemm_mixed_rem_cols(int m, int n) {
 // matrix cores best (about 1.13 PFLOP/s measured when all 256 compute units have a tile) but its
 // workgroups run in rounds of 256; the 128x128 tile (two workgroups per compute unit, about
 // 0.92 PFLOP/s) fills the chip in half-rounds of 256.  Pick the larger estimated throughput.
-int gemm_pick_tile(int m, int n, int splits) {
+int gemm_pick_tile(int m, int n, int splits, bool allow_192) {
     if (n % 256 != 0) return 0;
+    auto util = [](double tiles) { return tiles / (std::ceil(tiles / 256.0) * 256.0); };
     const double big = (double)(ceil_div(m, 256) * (int64_t)(n / 256) * splits);
     const double small = (double)(ceil_div(m, 128) * (int64_t)(n / 128) * splits);
-    const double big_util = big / (std::ceil(big / 256.0) * 256.0);
-    const double small_util = small / (std::ceil(small / 256.0) * 256.0);
-    return 1.13 * big_util >= 0.92 * small_util ? 3 : 0;
+    double best = 1.13 * util(big);
+    int tile = 3;
+    if (0.92 * util(small) > best) { best = 0.92 * util(small); tile = 0; }
+    // 256x192 (4 waves, about 0.88 PFLOP/s): for widths like 6144 = 32 x 192 that 256 divides into too few tiles
+    if (allow_192 && n % 192 == 0) {
+        const double mid = (double)(ceil_div(m, 256) * (int64_t)(n / 192) * splits);
+        if (0.88 * util(mid) > best) { best = 0.88 * util(mid); tile = 5; }
+    }
+    return tile;
 }
 
 // Split-K factor for a GEMM whose consumer can sum partial outputs: enough workgroups to give every
@@ -388,7 +400,7 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
                             int m, int n, int k, int mode, int tile, int splits, int64_t split_stride,
                             hipStream_t stream) {
     if (m <= 0) return hipSuccess;
-    if (n <= 0 || k <= 0 || n % 128 != 0 || k % BK != 0) return hipErrorInvalidValue;
+    if (n <= 0 || k <= 0 || n % 64 != 0 || k % BK != 0) return hipErrorInvalidValue;
     if (lda * 16 >= (int64_t)1 << 31 || ldw * 16 >= (int64_t)1 << 31) return hipErrorInvalidValue;
     if (splits < 1 || (k / BK) % splits != 0) return hipErrorInvalidValue;
     if (splits > 1 && mode != GEMM_STORE_F32) return hipErrorInvalidValue;
@@ -406,7 +418,7 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             default: return hipErrorInvalidValue;
         }
     }
-    if (tile < 0) tile = gemm_pick_tile(m, n, splits);
+    if (tile < 0) tile = gemm_pick_tile(m, n, splits, mode != GEMM_SWIGLU_BF16);
     switch (mode) {
         case GEMM_STORE_F32:
             return launch_mode<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, tile, splits, split_stride, stream);

@@ -80,6 +80,22 @@ def test_rmsnorm(T, H):
     assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 * 1.01 + 1e-6)
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 768, 192), (2, 192, 64), (513, 1536, 128)])
+def test_gemm_256x192_tile(M, N, K):
+    print(f"gemm 256x192 tile M={M} N={N} K={K}", flush=True)
+    a = rand_bits(6, 1, (M, K), 1.0)
+    w = rand_bits(6, 2, (N, K), 0.05)
+    ref = oracle.linear(oracle.bf16_to_f64(a), w)
+    Mp = (M + 255) // 256 * 256
+    out = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV)
+    wpad = np.zeros(((N + 255) // 256 * 256, K), dtype=np.uint16); wpad[:N] = w
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(wpad), out, M, N, K, B.GEMM_STORE_F32, 5)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(wpad), out, M, N, K, B.GEMM_ADD_F32, 5)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.abs(got - 2 * ref).max() <= 4e-5 * np.abs(ref).max() + 1e-6
+
+
 @pytest.mark.parametrize("tile", [-1, 4])
 @pytest.mark.parametrize("mode", ["store", "swiglu"])
 def test_gemm_mixed_tile_launch(mode, tile):
