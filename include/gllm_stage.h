@@ -177,6 +177,13 @@ const char* gllm_profile_class_name(int32_t i);
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
                               int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream);
 
+/* Split-K form of the store mode: split s (0 <= s < splits) multiplies the k range [s*k/splits, (s+1)*k/splits)
+ * and stores its partial product to out + s*plane_stride floats; the caller sums the planes.  k/64 must be a
+ * multiple of splits. */
+gllm_status gllm_op_gemm_bf16_splitk(const void* a, int64_t lda, const void* w, int64_t ldw, float* out, int64_t ldc,
+                                     int32_t m, int32_t n, int32_t k, int32_t tile, int32_t splits, int64_t plane_stride,
+                                     void* stream);
+
 /* h[t][j] = bf16(x[t][j] * rsqrt(mean_j x^2 + eps) * gamma[j]); x fp32 [rows][hidden]. */
 gllm_status gllm_op_rmsnorm(const float* x, const void* gamma_bf16, void* h_bf16, int32_t rows, int32_t hidden,
                             double eps, void* stream);

@@ -25,7 +25,7 @@ EXPORTS = [
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
     "gllm_stage_bind_kv_pool", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
-    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
+    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
 ]
 
 
@@ -105,6 +105,8 @@ def load_library():
     lib.gllm_profile_class_name.argtypes = [i32]
     lib.gllm_op_gemm_bf16.restype = i32
     lib.gllm_op_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
+    lib.gllm_op_gemm_bf16_splitk.restype = i32
+    lib.gllm_op_gemm_bf16_splitk.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, i64, vp]
     lib.gllm_op_rmsnorm.restype = i32
     lib.gllm_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_double, vp]
     lib.gllm_op_peak_mfma.restype = i32
@@ -222,6 +224,16 @@ def gllm_op_gemm_bf16(a, w, out, m: int, n: int, k: int, mode: int, tile: int = 
                                ldc or out.stride(0), m, n, k, mode, tile, _stream_ptr(stream))
     if st != GLLM_OK:
         raise GllmError(st, "gllm_op_gemm_bf16")
+
+
+def gllm_op_gemm_bf16_splitk(a, w, out_planes, m: int, n: int, k: int, tile: int, splits: int, stream=None):
+    """out_planes: fp32 [splits, m, n]."""
+    lib = load_library()
+    st = lib.gllm_op_gemm_bf16_splitk(a.data_ptr(), a.stride(0), w.data_ptr(), w.stride(0), out_planes.data_ptr(),
+                                      out_planes.stride(1), m, n, k, tile, splits, out_planes.stride(0),
+                                      _stream_ptr(stream))
+    if st != GLLM_OK:
+        raise GllmError(st, "gllm_op_gemm_bf16_splitk")
 
 
 def gllm_op_rmsnorm(x, gamma, h, eps: float, stream=None):

@@ -38,9 +38,10 @@ enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,
                             int m, int n, int k, int mode, int tile, int splits, int64_t split_stride,
                             hipStream_t stream);
-int gemm_pick_tile(int m, int n, int splits, bool allow_192);
 int gemm_mixed_rem_cols(int m, int n);
-int gemm_pick_splits(int m, int n, int k);
+// Tile id and split-K factor the cost model prefers (splits stays 1 unless mode is GEMM_STORE_F32).
+struct GemmPlan { int tile; int splits; };
+GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits);
 
 // Residual stream entry: x = float(in_bf16), h = bf16(rmsnorm(x) * gamma).
 hipError_t launch_rmsnorm_from_bf16(const bf16_t* in, float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh,
@@ -60,8 +61,10 @@ hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, 
                                int64_t ld_dst, hipStream_t stream);
 
 struct RopeKvArgs {
-    const float* qkv;        // [T][ld_qkv] fp32: q heads, then k heads, then v heads
+    const float* qkv;        // planes x [T][ld_qkv] fp32: q heads, then k heads, then v heads; planes are summed
     int64_t ld_qkv;
+    int planes;
+    int64_t plane_stride;
     const bf16_t* bias;      // [n_qkv] or null
     const float* rope_cs;    // [max_position][d/2][2] (cos, sin)
     const int32_t* tok_pos;  // [T]

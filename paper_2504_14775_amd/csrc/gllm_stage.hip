@@ -38,7 +38,7 @@ struct LayerBuffers {
 };
 
 constexpr int kStagingSlots = 4;
-constexpr int kMaxSplits = 4;
+constexpr int kMaxSplits = 8;
 
 struct MetaLayout {  // offsets in bytes inside the metadata block (host staging and device copy alike)
     size_t tok_pos, tok_page, bt_flat, dec_items, dec_rows, pre_items, total;
@@ -121,7 +121,7 @@ size_t workspace_layout(gllm_stage* s, unsigned char* base) {
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return base ? base + o : nullptr; };
     s->x = (float*)take((size_t)c.max_tokens * c.hidden * 4);
     s->h = (bf16_t*)take((size_t)s->m_pad * c.hidden * 2);
-    s->qkv = (float*)take((size_t)c.max_tokens * s->n_qkv_pad * 4);
+    s->qkv = (float*)take((size_t)kMaxSplits * c.max_tokens * s->n_qkv_pad * 4);
     s->q = (bf16_t*)take((size_t)c.max_tokens * s->q_dim * 2);
     s->attn = (bf16_t*)take((size_t)s->m_pad * s->q_dim * 2);
     s->act = (bf16_t*)take((size_t)s->m_pad * s->inter_pad * 2);
@@ -544,8 +544,12 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     const int64_t pool_layer = (int64_t)s->num_blocks * c.n_kv_heads * kPage * d;
     const float eps = (float)c.rms_eps;
     const int64_t y_plane = (int64_t)c.max_tokens * H;
-    const int split_o = std::min(kMaxSplits, gemm_pick_splits(Ti, H, s->q_dim));
-    const int split_d = std::min(kMaxSplits, gemm_pick_splits(Ti, H, s->inter_pad));
+    // tile shapes and split-K factors for this batch size (the consumers sum the partial planes in order)
+    const GemmPlan plan_qkv = gemm_plan(Ti, s->n_qkv_pad, H, GEMM_STORE_F32, kMaxSplits);
+    const GemmPlan plan_o = gemm_plan(Ti, H, s->q_dim, GEMM_STORE_F32, kMaxSplits);
+    const GemmPlan plan_d = gemm_plan(Ti, H, s->inter_pad, GEMM_STORE_F32, kMaxSplits);
+    const int split_o = plan_o.splits, split_d = plan_d.splits;
+    const int64_t qkv_plane = (int64_t)c.max_tokens * s->n_qkv_pad;
     int pending = 0;  // planes of y still to be added to the residual stream
     for (int l = 0; l < c.num_layers; ++l) {
         const LayerBuffers& L = s->layers[l];
@@ -556,12 +560,13 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         }
         {
             ProfScope ps(s, st, PC_GEMM_QKV);
-            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wqkv, H, s->qkv, s->n_qkv_pad, Ti, s->n_qkv_pad, H, GEMM_STORE_F32, -1, 1, 0, st));
+            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wqkv, H, s->qkv, s->n_qkv_pad, Ti, s->n_qkv_pad, H, GEMM_STORE_F32, plan_qkv.tile,
+                                        plan_qkv.splits, qkv_plane, st));
         }
         {
             ProfScope ps(s, st, PC_ROPE_KV);
             RopeKvArgs a{};
-            a.qkv = s->qkv; a.ld_qkv = s->n_qkv_pad;
+            a.qkv = s->qkv; a.ld_qkv = s->n_qkv_pad; a.planes = plan_qkv.splits; a.plane_stride = qkv_plane;
             a.bias = c.has_qkv_bias ? L.bias : nullptr;
             a.rope_cs = s->rope_cs; a.tok_pos = d_tok_pos; a.tok_page = d_tok_page;
             a.q_out = s->q; a.ld_q = s->q_dim;
@@ -600,7 +605,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         {
             // the projection writes split_o partial products; the next RMSNorm adds them to the residual stream
             ProfScope ps(s, st, PC_GEMM_O);
-            HIP_TRY(s, launch_gemm_bf16(s->attn, s->q_dim, L.wo, s->q_dim, s->y, H, Ti, H, s->q_dim, GEMM_STORE_F32, -1, split_o, y_plane, st));
+            HIP_TRY(s, launch_gemm_bf16(s->attn, s->q_dim, L.wo, s->q_dim, s->y, H, Ti, H, s->q_dim, GEMM_STORE_F32, plan_o.tile, split_o, y_plane, st));
         }
         {
             ProfScope ps(s, st, PC_RMSNORM);
@@ -612,7 +617,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         }
         {
             ProfScope ps(s, st, PC_GEMM_DOWN);
-            HIP_TRY(s, launch_gemm_bf16(s->act, s->inter_pad, L.wd, s->inter_pad, s->y, H, Ti, H, s->inter_pad, GEMM_STORE_F32, -1, split_d, y_plane, st));
+            HIP_TRY(s, launch_gemm_bf16(s->act, s->inter_pad, L.wd, s->inter_pad, s->y, H, Ti, H, s->inter_pad, GEMM_STORE_F32, plan_d.tile, split_d, y_plane, st));
         }
         pending = split_d;
     }
@@ -627,6 +632,15 @@ gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t
                               int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream) {
     if (!a || !w || !out) return GLLM_E_INVALID;
     hipError_t e = launch_gemm_bf16((const bf16_t*)a, lda, (const bf16_t*)w, ldw, out, ldc, m, n, k, mode, tile, 1, 0, (hipStream_t)stream);
+    return e == hipSuccess ? GLLM_OK : (e == hipErrorInvalidValue ? GLLM_E_UNSUPPORTED : GLLM_E_HIP);
+}
+
+gllm_status gllm_op_gemm_bf16_splitk(const void* a, int64_t lda, const void* w, int64_t ldw, float* out, int64_t ldc,
+                                     int32_t m, int32_t n, int32_t k, int32_t tile, int32_t splits, int64_t plane_stride,
+                                     void* stream) {
+    if (!a || !w || !out) return GLLM_E_INVALID;
+    hipError_t e = launch_gemm_bf16((const bf16_t*)a, lda, (const bf16_t*)w, ldw, out, ldc, m, n, k, GEMM_STORE_F32, tile,
+                                    splits, plane_stride, (hipStream_t)stream);
     return e == hipSuccess ? GLLM_OK : (e == hipErrorInvalidValue ? GLLM_E_UNSUPPORTED : GLLM_E_HIP);
 }
 

@@ -38,7 +38,7 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 // The work of one workgroup: output tile number `wg_linear` of a tiles_m x tiles_n grid of BM x BN tiles
 // whose first column is n_base.
-template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
+template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0, int NS = 2>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
                                           int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
                                           int tiles_m, int tiles_n, int n_base, int wg_linear,
@@ -161,13 +161,18 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     // boundary: the barrier sits before the last k-step of a tile, after which the next tile's first
     // fragments are fetched under the MFMAs of that last k-step.
     constexpr int KK = BK / 16;
-    issue_loads(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (KT > 1) issue_loads(1, 1);
+    static_assert((NS - 1) * GPW < 64, "outstanding loads must fit the vmcnt field");
+    // NS LDS stages: tiles kt+1 .. kt+NS-1 are in flight while tile kt is multiplied (NS = 2 for the large
+    // tiles, which fill LDS; more stages for the small tile when the operands stream from HBM).  Loads past the
+    // last tile re-read it into a stage nobody reads again, so every iteration issues the same number of loads
+    // and the wait counts are compile-time constants.
+#pragma unroll
+    for (int i = 0; i < NS; ++i) issue_loads(min(i, KT - 1), i);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * GPW) : "memory");
+    __builtin_amdgcn_s_barrier();
     load_frags(0, 0, 0);
     for (int kt = 0; kt < KT - 1; ++kt) {
-        const int stage = kt & 1;
+        const int stage = kt % NS;
 #pragma unroll
         for (int kk = 0; kk < KK - 1; ++kk) {
             if (!(DBG & 1)) load_frags(stage, kk + 1, (kk + 1) & 1);
@@ -175,18 +180,21 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
             interleave();
         }
         if (!(DBG & 2)) {
-            if (!(DBG & 4)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();  // tile kt+1 has landed everywhere; every wave holds its last fragments of tile kt
+            // tile kt+1 must have landed (tiles kt+2 .. kt+NS-1 may still be in flight) and this wave's last
+            // fragments of tile kt must be in registers before anybody overwrites the stage
+            if (!(DBG & 4)) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * GPW) : "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
         }
-        // branch-free tail (one scheduling region): the loads of tile kt+2 (past the end: the last tile once
-        // more, into the stage nobody reads again), the first fragments of tile kt+1, the last MFMAs of tile kt
-        if (!(DBG & 16)) issue_loads(min(kt + 2, KT - 1), stage);
-        if (!(DBG & 1)) load_frags(stage ^ 1, 0, KK & 1);
+        // branch-free tail (one scheduling region): the loads of tile kt+NS into the stage just vacated, the
+        // first fragments of tile kt+1, the last MFMAs of tile kt
+        if (!(DBG & 16)) issue_loads(min(kt + NS, KT - 1), stage);
+        if (!(DBG & 1)) load_frags((kt + 1) % NS, 0, KK & 1);
         mfmas((KK - 1) & 1);
         interleave_with_loads();
     }
     {
-        const int stage = (KT - 1) & 1;
+        const int stage = (KT - 1) % NS;
 #pragma unroll
         for (int kk = 0; kk < KK - 1; ++kk) {
             load_frags(stage, kk + 1, (kk + 1) & 1);
@@ -216,10 +224,11 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     constexpr int LPR = C / 4;                                      // lanes per row on the way out
     constexpr int RPI = 64 / LPR;                                   // rows per read instruction (lanes >= RPI*LPR idle)
     static_assert(32 % RPI == 0, "a slab must be a whole number of read instructions");
-    static_assert(NW * 32 * CS * 4 <= 2 * STAGE_BYTES, "epilogue slab must fit in the tile buffers");
+    static_assert(NW * 32 * CS * 4 <= NS * STAGE_BYTES, "epilogue slab must fit in the tile buffers");
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * CS);
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
     const int orow = lane / LPR, ocol = (lane % LPR) * 4;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the redundant tail loads have landed too
     __syncthreads();  // all waves have finished reading the last tile
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -264,14 +273,14 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
+template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0, int NS = 2>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ W, int64_t ldw,
                                                                     void* __restrict__ out, int64_t ldc, int M,
                                                                     int K, int tiles_m, int tiles_n,
                                                                     int64_t split_stride) {
-    gemm_tile<BM, BN, WGM, WGN, MODE, DBG>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, blockIdx.x,
-                                           split_stride);
+    gemm_tile<BM, BN, WGM, WGN, MODE, DBG, NS>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, blockIdx.x,
+                                               split_stride);
 }
 
 // Two tile shapes in one launch: the first big_tiles workgroups cover columns [0, n_split) with 256x256
@@ -290,13 +299,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_mixed_kernel(const bf16_t* __re
                                         blockIdx.x - big_tiles, 0);
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0>
+template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0, int NS = 2>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                        int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
     if (n % BN != 0) return hipErrorInvalidValue;
     const int tiles_m = (int)ceil_div(m, BM), tiles_n = n / BN;
-    const size_t smem = 2 * (BM + BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, DBG>;
+    const size_t smem = NS * (BM + BN) * BK * sizeof(bf16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, DBG, NS>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -318,6 +327,7 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 1: return launch_tile<256, 128, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 2: return launch_tile<256, 256, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
+        case 6: return launch_tile<128, 128, 2, 2, MODE, 0, 4>(GLLM_TILE_ARGS);
         case 5:
             if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 2, 2, MODE>(GLLM_TILE_ARGS);
             else return hipErrorInvalidValue;
@@ -366,34 +376,39 @@ int gemm_mixed_rem_cols(int m, int n) {
     return rem / tiles_m;
 }
 
-// Tile shape for a problem.  The 256x256 tile (8 waves, one workgroup per compute unit) feeds the
-// matrix cores best (about 1.13 PFLOP/s measured when all 256 compute units have a tile) but its
-// workgroups run in rounds of 256; the 128x128 tile (two workgroups per compute unit, about
-// 0.92 PFLOP/s) fills the chip in half-rounds of 256.  Pick the larger estimated throughput.
-int gemm_pick_tile(int m, int n, int splits, bool allow_192) {
-    if (n % 256 != 0) return 0;
-    auto util = [](double tiles) { return tiles / (std::ceil(tiles / 256.0) * 256.0); };
-    const double big = (double)(ceil_div(m, 256) * (int64_t)(n / 256) * splits);
-    const double small = (double)(ceil_div(m, 128) * (int64_t)(n / 128) * splits);
-    double best = 1.13 * util(big);
-    int tile = 3;
-    if (0.92 * util(small) > best) { best = 0.92 * util(small); tile = 0; }
-    // 256x192 (4 waves, about 0.88 PFLOP/s): for widths like 6144 = 32 x 192 that 256 divides into too few tiles
-    if (allow_192 && n % 192 == 0) {
-        const double mid = (double)(ceil_div(m, 256) * (int64_t)(n / 192) * splits);
-        if (0.88 * util(mid) > best) { best = 0.88 * util(mid); tile = 5; }
+// Tile shape and split-K factor for a problem, from a small cost model fitted to measurements on MI355X.
+// Unit: the time of one k-step of a 256x256 tile (~1.65 us).  A 256x256 tile (8 waves, one workgroup per
+// compute unit) costs k_steps + 6 (prologue, epilogue) per round of 256 tiles; a 128x128 tile costs
+// 0.605 k_steps + 2 per round of 512 tiles when two share a compute unit, 0.43 k_steps + 2 when alone.
+// A partial last round of 256x256 tiles that covers at most half of the compute units can be run with
+// half-width tiles instead (mixed launch, ~0.55 of a round).  Split-K multiplies the number of tiles and
+// divides the k-steps, at the price of writing one fp32 plane per split (mostly hidden under other tiles).
+GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
+    const int its = k / BK;
+    GemmPlan best{0, 1};
+    double best_cost = 1e30;
+    if (mode != GEMM_STORE_F32) max_splits = 1;
+    for (int s = 1; s <= max_splits; s *= 2) {
+        if (its % s != 0 || (s > 1 && its / s < 8)) continue;
+        const double steps = (double)its / s;
+        const double plane_cost = (double)m * n * 4.0 * s / 8e12 / 1.65e-6;  // mostly hidden under other tiles
+        if (n % 256 == 0) {
+            const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 256) * s;
+            const bool mixed = s == 1 && gemm_mixed_rem_cols(m, n) > 0;
+            const double rounds = mixed ? (double)(tiles / 256) + 0.55 : (double)ceil_div(tiles, 256);
+            const double cost = rounds * (steps + 6.0) + plane_cost;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{mixed ? 4 : 3, s}; }
+        }
+        if (n % 128 == 0) {
+            const int64_t tiles = ceil_div(m, 128) * (int64_t)(n / 128) * s;
+            const int64_t full = tiles / 512, rem = tiles % 512;
+            double cost = (double)full * (steps * 0.605 + 2.0) + plane_cost;
+            if (rem > 256) cost += steps * 0.605 + 2.0;
+            else if (rem > 0) cost += steps * 0.43 + 2.0;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{0, s}; }
+        }
     }
-    return tile;
-}
-
-// Split-K factor for a GEMM whose consumer can sum partial outputs: enough workgroups to give every
-// compute unit a 256x256 tile, as long as each share of k keeps at least 16 steps of 64.
-int gemm_pick_splits(int m, int n, int k) {
-    if (n % 256 != 0) return 1;
-    const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 256);
-    int s = 1;
-    while (s < 4 && tiles * s < 192 && (k / BK) % (s * 2) == 0 && (k / BK) / (s * 2) >= 16) s *= 2;
-    return s;
+    return best;
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,
@@ -404,9 +419,17 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
     if (lda * 16 >= (int64_t)1 << 31 || ldw * 16 >= (int64_t)1 << 31) return hipErrorInvalidValue;
     if (splits < 1 || (k / BK) % splits != 0) return hipErrorInvalidValue;
     if (splits > 1 && mode != GEMM_STORE_F32) return hipErrorInvalidValue;
-    if (tile < 0 && splits == 1) {
-        const int rem_cols = gemm_mixed_rem_cols(m, n);
-        if (rem_cols > 0) tile = 4;
+    if (tile < 0) {
+        tile = gemm_plan(m, n, k, splits == 1 ? mode : GEMM_ADD_F32, 1).tile;  // tile for the given split count
+        if (splits > 1) {
+            // splits fixed by the caller: compare the two tile shapes at that split count
+            const int64_t t3 = ceil_div(m, 256) * (int64_t)(n / 256) * splits, t0 = ceil_div(m, 128) * (int64_t)(n / 128) * splits;
+            const double steps = (double)(k / BK) / splits;
+            const double c3 = n % 256 == 0 ? (double)ceil_div(t3, 256) * (steps + 6.0) : 1e30;
+            const double c0 = (double)(t0 / 512) * (steps * 0.605 + 2.0) +
+                              (t0 % 512 > 256 ? steps * 0.605 + 2.0 : t0 % 512 > 0 ? steps * 0.43 + 2.0 : 0.0);
+            tile = c3 <= c0 ? 3 : 0;
+        }
     }
     if (tile == 4) {  // mixed 256x256 / 256x128 launch
         const int rem_cols = gemm_mixed_rem_cols(m, n);
@@ -418,7 +441,6 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             default: return hipErrorInvalidValue;
         }
     }
-    if (tile < 0) tile = gemm_pick_tile(m, n, splits, mode != GEMM_SWIGLU_BF16);
     switch (mode) {
         case GEMM_STORE_F32:
             return launch_mode<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, tile, splits, split_stride, stream);

@@ -129,6 +129,10 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
         const int hd = ii / half, j = ii % half;
         const int col = (is_q ? 0 : k_col0) + hd * d + j;
         float lo = row[col], hi = row[col + half];
+        for (int p = 1; p < a.planes; ++p) {
+            lo += row[p * a.plane_stride + col];
+            hi += row[p * a.plane_stride + col + half];
+        }
         if (a.bias) {
             lo += (float)a.bias[col];
             hi += (float)a.bias[col + half];
@@ -151,6 +155,7 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
     for (int i = threadIdx.x; i < v_elems; i += 256) {
         const int hd = i / d, e = i % d;
         float v = row[v_col0 + i];
+        for (int p = 1; p < a.planes; ++p) v += row[p * a.plane_stride + v_col0 + i];
         if (a.bias) v += (float)a.bias[v_col0 + i];
         bf16_t* vb = a.v_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage);
         vb[e * kPage + slot] = (bf16_t)v;

@@ -22,7 +22,7 @@ def padded_rows(bits, rows):
     return out
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6])
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (52, 512, 256), (300, 768, 192), (257, 1280, 704), (1024, 256, 2048)])
 def test_gemm_store_and_add(M, N, K, tile):
     print(f"gemm store/add M={M} N={N} K={K} tile={tile}", flush=True)
@@ -43,7 +43,7 @@ def test_gemm_store_and_add(M, N, K, tile):
     assert np.abs(got2 - 2 * ref).max() <= 4e-5 * scale + 1e-6
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6])
 @pytest.mark.parametrize("M,I,K", [(52, 768, 256), (130, 128, 128), (300, 1408, 320)])
 def test_gemm_swiglu(M, I, K, tile):
     print(f"gemm swiglu M={M} I={I} K={K} tile={tile}", flush=True)
@@ -127,3 +127,23 @@ def test_gemm_mixed_tile_launch(mode, tile):
         torch.cuda.synchronize()
         got = oracle.bf16_to_f64(bits_of(out))
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-4)
+
+
+@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2)])
+def test_gemm_split_k_planes_sum_to_the_product(tile, splits):
+    M, N, K = 300, 512, 1024
+    print(f"gemm split-K tile={tile} splits={splits}", flush=True)
+    a = rand_bits(7, 1, (M, K), 1.0)
+    w = rand_bits(7, 2, (N, K), 0.05)
+    ref = oracle.linear(oracle.bf16_to_f64(a), w)
+    Mp = (M + 255) // 256 * 256
+    planes = torch.full((splits, M, N), 9.0, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16_splitk(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w), planes, M, N, K, tile, splits)
+    torch.cuda.synchronize()
+    got = planes.cpu().numpy().astype(np.float64)
+    assert np.abs(got.sum(axis=0) - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-6
+    # each plane is the product over its own share of k
+    x = oracle.bf16_to_f64(a)
+    ks = K // splits
+    part0 = oracle.linear(x[:, :ks], np.ascontiguousarray(w[:, :ks]))
+    assert np.abs(got[0] - part0).max() <= 2e-5 * np.abs(part0).max() + 1e-6
