@@ -38,7 +38,8 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 // The work of one workgroup: output tile number `wg_linear` of a tiles_m x tiles_n grid of BM x BN tiles
 // whose first column is n_base.
-template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0, int NS = 2>
+// NS LDS stages of 64 k-values each (NS = 2 fills LDS for the 256x256 tile).
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
                                           int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
                                           int tiles_m, int tiles_n, int n_base, int wg_linear,
@@ -110,19 +111,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // operand reads: lane supplies row (lane % 32), k-group (lane / 32) of each 16-wide k step
-    const int frow = lane & 31, fgrp = lane >> 5, fsw = (frow >> 1) & 7, fpar = (frow & 1) * 8;
-    const int a_off = (wm * WTM + (frow & ~1)) * (BK * 2);
-    const int w_off = (BM + wn * WTN + (frow & ~1)) * (BK * 2);
+    const int frow = lane & 31, fgrp = lane >> 5;
     bf16x8 fa[2][TM], fw[2][TN];
-    auto load_frags = [&](int stage, int kk, int buf) {
-        const unsigned char* sa = smem + stage * STAGE_BYTES + a_off;
-        const unsigned char* sw = smem + stage * STAGE_BYTES + w_off;
-        const int g = ((fpar + kk * 2 + fgrp) ^ fsw) * 16;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * (BK * 2) + g);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fw[buf][j] = *reinterpret_cast<const bf16x8*>(sw + j * 32 * (BK * 2) + g);
-    };
     auto mfmas = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -130,95 +120,95 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fw[buf][j], acc[i][j], 0, 0, 0);
     };
-    // scheduling hint for one "fetch fragments of the next k-step, multiply the current one" step:
-    // spread the LDS reads between the MFMAs so that their latency is covered
     constexpr int kReads = TM + TN, kMfma = TM * TN;
     constexpr int kPaired = kReads < kMfma ? kReads : kMfma;
-    auto interleave = [&]() {
-        // reads first, one per MFMA, so that the MFMAs left over cover the latency of the last read
-#pragma unroll
-        for (int r = 0; r < kPaired; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA (first, so that the wait for the
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // previous reads precedes every new read)
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, kReads - kPaired, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kPaired, 0);
-    };
-    // the step after the barrier also issues the next tile's global loads: one per MFMA, so that the
-    // matrix cores keep running while the loads are handed to the memory pipeline
-    constexpr int kLoadsPerMfma = (GPW + kMfma - 1) / kMfma;
-    auto interleave_with_loads = [&]() {
-#pragma unroll
-        for (int r = 0; r < kMfma; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (r * kLoadsPerMfma < GPW) __builtin_amdgcn_sched_group_barrier(0x020, kLoadsPerMfma, 0);
-            if (r < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-    };
 
-    // Software pipeline.  Global: tile kt+1 is in flight while tile kt is multiplied.  LDS -> registers:
-    // the fragments of k-step kk+1 are fetched while k-step kk is multiplied, also across the tile
-    // boundary: the barrier sits before the last k-step of a tile, after which the next tile's first
-    // fragments are fetched under the MFMAs of that last k-step.
-    constexpr int KK = BK / 16;
-    static_assert((NS - 1) * GPW < 64, "outstanding loads must fit the vmcnt field");
-    // NS LDS stages: tiles kt+1 .. kt+NS-1 are in flight while tile kt is multiplied (NS = 2 for the large
-    // tiles, which fill LDS; more stages for the small tile when the operands stream from HBM).  Loads past the
-    // last tile re-read it into a stage nobody reads again, so every iteration issues the same number of loads
-    // and the wait counts are compile-time constants.
+    {
+        const int fsw = (frow >> 1) & 7, fpar = (frow & 1) * 8;
+        const int a_off = (wm * WTM + (frow & ~1)) * (BK * 2);
+        const int w_off = (BM + wn * WTN + (frow & ~1)) * (BK * 2);
+        auto load_frags = [&](int stage, int kk, int buf) {
+            const unsigned char* sa = smem + stage * STAGE_BYTES + a_off;
+            const unsigned char* sw = smem + stage * STAGE_BYTES + w_off;
+            const int g = ((fpar + kk * 2 + fgrp) ^ fsw) * 16;
 #pragma unroll
-    for (int i = 0; i < NS; ++i) issue_loads(min(i, KT - 1), i);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * GPW) : "memory");
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, 0);
-    for (int kt = 0; kt < KT - 1; ++kt) {
-        const int stage = kt % NS;
+            for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * (BK * 2) + g);
 #pragma unroll
-        for (int kk = 0; kk < KK - 1; ++kk) {
-            if (!(DBG & 1)) load_frags(stage, kk + 1, (kk + 1) & 1);
-            mfmas(kk & 1);
-            interleave();
-        }
-        if (!(DBG & 2)) {
+            for (int j = 0; j < TN; ++j) fw[buf][j] = *reinterpret_cast<const bf16x8*>(sw + j * 32 * (BK * 2) + g);
+        };
+        // scheduling hint for one "fetch fragments of the next k-step, multiply the current one" step:
+        // spread the LDS reads between the MFMAs so that their latency is covered
+        auto interleave = [&]() {
+            // reads first, one per MFMA, so that the MFMAs left over cover the latency of the last read
+#pragma unroll
+            for (int r = 0; r < kPaired; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA (first, so that the wait for the
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // previous reads precedes every new read)
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, kReads - kPaired, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kPaired, 0);
+        };
+        // the step after the barrier also issues the next tile's global loads: one per MFMA, so that the
+        // matrix cores keep running while the loads are handed to the memory pipeline
+        constexpr int kLoadsPerMfma = (GPW + kMfma - 1) / kMfma;
+        auto interleave_with_loads = [&]() {
+#pragma unroll
+            for (int r = 0; r < kMfma; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (r * kLoadsPerMfma < GPW) __builtin_amdgcn_sched_group_barrier(0x020, kLoadsPerMfma, 0);
+                if (r < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        };
+
+        // Software pipeline.  Global: tiles kt+1 .. kt+NS-1 are in flight while tile kt is multiplied (NS = 2
+        // for the large tiles, which fill LDS; more stages for the small tile when the operands stream from
+        // HBM).  LDS -> registers: the fragments of k-step kk+1 are fetched while k-step kk is multiplied, also
+        // across the tile boundary: the barrier sits before the last k-step of a tile, after which the next
+        // tile's first fragments are fetched under the MFMAs of that last k-step.  Loads past the last tile
+        // re-read it into a stage nobody reads again, so every iteration issues the same number of loads and
+        // the wait counts are compile-time constants.
+        constexpr int KK = BK / 16;
+        static_assert((NS - 1) * GPW < 64, "outstanding loads must fit the vmcnt field");
+#pragma unroll
+        for (int i = 0; i < NS; ++i) issue_loads(min(i, KT - 1), i);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * GPW) : "memory");
+        __builtin_amdgcn_s_barrier();
+        load_frags(0, 0, 0);
+        for (int kt = 0; kt < KT - 1; ++kt) {
+            const int stage = kt % NS;
+#pragma unroll
+            for (int kk = 0; kk < KK - 1; ++kk) {
+                load_frags(stage, kk + 1, (kk + 1) & 1);
+                mfmas(kk & 1);
+                interleave();
+            }
             // tile kt+1 must have landed (tiles kt+2 .. kt+NS-1 may still be in flight) and this wave's last
             // fragments of tile kt must be in registers before anybody overwrites the stage
-            if (!(DBG & 4)) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * GPW) : "memory");
-            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * GPW) : "memory");
             __builtin_amdgcn_s_barrier();
+            // branch-free tail (one scheduling region): the loads of tile kt+NS into the stage just vacated,
+            // the first fragments of tile kt+1, the last MFMAs of tile kt
+            issue_loads(min(kt + NS, KT - 1), stage);
+            load_frags((kt + 1) % NS, 0, KK & 1);
+            mfmas((KK - 1) & 1);
+            interleave_with_loads();
         }
-        // branch-free tail (one scheduling region): the loads of tile kt+NS into the stage just vacated, the
-        // first fragments of tile kt+1, the last MFMAs of tile kt
-        if (!(DBG & 16)) issue_loads(min(kt + NS, KT - 1), stage);
-        if (!(DBG & 1)) load_frags((kt + 1) % NS, 0, KK & 1);
-        mfmas((KK - 1) & 1);
-        interleave_with_loads();
-    }
-    {
-        const int stage = (KT - 1) % NS;
+        {
+            const int stage = (KT - 1) % NS;
 #pragma unroll
-        for (int kk = 0; kk < KK - 1; ++kk) {
-            load_frags(stage, kk + 1, (kk + 1) & 1);
-            mfmas(kk & 1);
-            interleave();
+            for (int kk = 0; kk < KK - 1; ++kk) {
+                load_frags(stage, kk + 1, (kk + 1) & 1);
+                mfmas(kk & 1);
+                interleave();
+            }
+            mfmas((KK - 1) & 1);
         }
-        mfmas((KK - 1) & 1);
-    }
-
-    if (DBG & 8) {  // timing experiment: no epilogue (one store keeps the accumulators alive)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no LDS fill may outlive the workgroup
-        float s0 = 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) s0 += acc[i][j][0] + acc[i][j][7];
-        if (s0 == 1234.5f) reinterpret_cast<float*>(out)[0] = s0;
-        return;
     }
 
     // ---- epilogue, staged through LDS so that every global access is a 16-byte piece of a long row
     // segment.  Accumulator element v of a 32x32 block sits at row 8*(v/4) + 4*(lane/32) + v%4, column
     // lane%32; a wave writes one 32-row slab of its tile to its private LDS area, then reads it back row
-    // by row, 4 consecutive columns per lane.
+    // by row, 4 consecutive columns per lane.  Only the first barrier is needed (the slabs overlay the tiles).
     constexpr int C = (MODE == GEMM_SWIGLU_BF16) ? WTN / 2 : WTN;  // result columns of a wave slab
     constexpr int CS = C + 8;                                       // padded row stride (floats)
     constexpr int LPR = C / 4;                                      // lanes per row on the way out
@@ -247,40 +237,40 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
                 for (int v = 0; v < 16; ++v)
                     slab[(8 * (v / 4) + row_in + (v % 4)) * CS + j * 32 + col_in] = acc[i][j][v];
         }
-        __syncthreads();
+        // the slab is private to the wave and LDS executes a wave's instructions in order: no barrier needed
         const int mrow0 = m0 + wm * WTM + i * 32;
+        const bool lane_on = RPI * LPR == 64 || lane < RPI * LPR;
+        f32x4 val[32 / RPI];
+#pragma unroll
+        for (int r = 0; r < 32; r += RPI)  // all reads first, so that their latencies overlap
+            val[r / RPI] = *reinterpret_cast<const f32x4*>(slab + (r + (lane_on ? orow : 0)) * CS + (lane_on ? ocol : 0));
 #pragma unroll
         for (int r = 0; r < 32; r += RPI) {
             const int m = mrow0 + r + orow;
-            if (RPI * LPR < 64 && lane >= RPI * LPR) continue;
-            const f32x4 val = *reinterpret_cast<const f32x4*>(slab + (r + orow) * CS + ocol);
-            if (m < M) {
-                if (MODE == GEMM_SWIGLU_BF16) {
-                    bf16_t* p = reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldc + (n0 + wn * WTN) / 2 + ocol;
-                    *reinterpret_cast<bf16x4*>(p) = __builtin_convertvector(val, bf16x4);
+            if (!lane_on || m >= M) continue;
+            if (MODE == GEMM_SWIGLU_BF16) {
+                bf16_t* p = reinterpret_cast<bf16_t*>(out) + (int64_t)m * ldc + (n0 + wn * WTN) / 2 + ocol;
+                *reinterpret_cast<bf16x4*>(p) = __builtin_convertvector(val[r / RPI], bf16x4);
+            } else {
+                float* p = reinterpret_cast<float*>(out) + split_off + (int64_t)m * ldc + n0 + wn * WTN + ocol;
+                if (MODE == GEMM_ADD_F32) {
+                    f32x4 old = *reinterpret_cast<const f32x4*>(p);
+                    *reinterpret_cast<f32x4*>(p) = old + val[r / RPI];
                 } else {
-                    float* p = reinterpret_cast<float*>(out) + split_off + (int64_t)m * ldc + n0 + wn * WTN + ocol;
-                    if (MODE == GEMM_ADD_F32) {
-                        f32x4 old = *reinterpret_cast<const f32x4*>(p);
-                        *reinterpret_cast<f32x4*>(p) = old + val;
-                    } else {
-                        *reinterpret_cast<f32x4*>(p) = val;
-                    }
+                    *reinterpret_cast<f32x4*>(p) = val[r / RPI];
                 }
             }
         }
-        __syncthreads();
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ W, int64_t ldw,
                                                                     void* __restrict__ out, int64_t ldc, int M,
                                                                     int K, int tiles_m, int tiles_n,
                                                                     int64_t split_stride) {
-    gemm_tile<BM, BN, WGM, WGN, MODE, DBG, NS>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, blockIdx.x,
-                                               split_stride);
+    gemm_tile<BM, BN, WGM, WGN, MODE, NS>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, blockIdx.x, split_stride);
 }
 
 // Two tile shapes in one launch: the first big_tiles workgroups cover columns [0, n_split) with 256x256
@@ -299,13 +289,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_mixed_kernel(const bf16_t* __re
                                         blockIdx.x - big_tiles, 0);
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int DBG = 0, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                        int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
     if (n % BN != 0) return hipErrorInvalidValue;
     const int tiles_m = (int)ceil_div(m, BM), tiles_n = n / BN;
     const size_t smem = NS * (BM + BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, DBG, NS>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, NS>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -327,18 +317,10 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 1: return launch_tile<256, 128, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 2: return launch_tile<256, 256, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
-        case 6: return launch_tile<128, 128, 2, 2, MODE, 0, 4>(GLLM_TILE_ARGS);
+        case 6: return launch_tile<128, 128, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
         case 5:
             if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 2, 2, MODE>(GLLM_TILE_ARGS);
             else return hipErrorInvalidValue;
-        case 8: return launch_tile<256, 256, 2, 2, MODE, 1>(GLLM_TILE_ARGS);
-        case 9: return launch_tile<256, 256, 2, 2, MODE, 2>(GLLM_TILE_ARGS);
-        case 10: return launch_tile<256, 256, 2, 2, MODE, 3>(GLLM_TILE_ARGS);
-        case 11: return launch_tile<256, 256, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
-        case 12: return launch_tile<256, 256, 2, 2, MODE, 8>(GLLM_TILE_ARGS);
-        case 13: return launch_tile<256, 256, 2, 2, MODE, 12>(GLLM_TILE_ARGS);
-        case 14: return launch_tile<256, 256, 2, 2, MODE, 11>(GLLM_TILE_ARGS);
-        case 15: return launch_tile<256, 256, 2, 2, MODE, 16>(GLLM_TILE_ARGS);
         default: return hipErrorInvalidValue;
     }
 #undef GLLM_TILE_ARGS
@@ -405,7 +387,11 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
             double cost = (double)full * (steps * 0.605 + 2.0) + plane_cost;
             if (rem > 256) cost += steps * 0.605 + 2.0;
             else if (rem > 0) cost += steps * 0.43 + 2.0;
-            if (cost < best_cost) { best_cost = cost; best = GemmPlan{0, s}; }
+            // few rows: the weights stream from HBM and every tile is alone on its compute unit; the 4-stage
+            // variant keeps three k-steps of loads in flight (measured +10..20 % there)
+            const bool deep = m <= 256 && tiles <= 256;
+            if (deep) cost *= 0.85;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{deep ? 6 : 0, s}; }
         }
     }
     return best;
@@ -428,7 +414,7 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             const double c3 = n % 256 == 0 ? (double)ceil_div(t3, 256) * (steps + 6.0) : 1e30;
             const double c0 = (double)(t0 / 512) * (steps * 0.605 + 2.0) +
                               (t0 % 512 > 256 ? steps * 0.605 + 2.0 : t0 % 512 > 0 ? steps * 0.43 + 2.0 : 0.0);
-            tile = c3 <= c0 ? 3 : 0;
+            tile = c3 <= c0 ? 3 : (m <= 256 && t0 <= 256) ? 6 : 0;
         }
     }
     if (tile == 4) {  // mixed 256x256 / 256x128 launch

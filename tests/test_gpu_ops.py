@@ -129,7 +129,7 @@ def test_gemm_mixed_tile_launch(mode, tile):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-4)
 
 
-@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2)])
+@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2), (6, 2)])
 def test_gemm_split_k_planes_sum_to_the_product(tile, splits):
     M, N, K = 300, 512, 1024
     print(f"gemm split-K tile={tile} splits={splits}", flush=True)
