@@ -136,8 +136,9 @@ gllm_status gllm_stage_bind_kv_pool(gllm_stage* stage, void* k_pool /*DEVICE*/, 
 gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);
 
 /* Tuning knobs (defaults are chosen for MI355X).  Known names:
- *   "decode_min_workgroups" (default 6144): the keys of decode rows are cut into equal partitions (256 ..
- *   16384 keys, powers of two) until partitions x KV heads reaches this many workgroups.
+ *   "decode_min_workgroups" (default 2048): a partition size (256 .. 16384 keys, a power of two) is chosen as
+ *   the largest for which partitions x KV heads reaches this many workgroups; a decode row with more keys than
+ *   that is cut into equal shares of whole 32-key blocks, and the longest shares are launched first.
  *   "overlap_attention" (default 1): prefill attention of a layer runs on an internal side stream next to
  *   decode attention (forked from and joined back into the caller's stream with events); 0 keeps every
  *   kernel on the caller's stream.  Per-kernel profiling always uses the single-stream order.

@@ -104,8 +104,9 @@ struct DecodeRow {
     int32_t num_items;
     int32_t pad;
 };
-hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
-                                   float* part_ml, hipStream_t stream);
+// order[i] = index of the item that workgroup group i works on (a permutation of 0 .. num_items-1)
+hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, const int32_t* order, int num_items,
+                                   float* part_o, float* part_ml, hipStream_t stream);
 hipError_t launch_decode_combine(const AttnArgs& a, const DecodeRow* rows, int num_rows, const float* part_o,
                                  const float* part_ml, hipStream_t stream);
 

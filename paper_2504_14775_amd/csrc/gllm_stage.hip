@@ -41,7 +41,7 @@ constexpr int kStagingSlots = 4;
 constexpr int kMaxSplits = 8;
 
 struct MetaLayout {  // offsets in bytes inside the metadata block (host staging and device copy alike)
-    size_t tok_pos, tok_page, bt_flat, dec_items, dec_rows, pre_items, total;
+    size_t tok_pos, tok_page, bt_flat, dec_items, dec_order, dec_rows, pre_items, total;
 };
 
 }  // namespace
@@ -84,7 +84,7 @@ struct gllm_stage {
     hipEvent_t fork_ev[8] = {}, join_ev[8] = {};
     bool overlap_attention = true;
     bool alias_check = true;
-    int64_t decode_min_workgroups = 6144;  // partition the keys of decode rows until at least this many workgroups exist
+    int64_t decode_min_workgroups = 2048;  // partition the keys of decode rows until at least this many workgroups exist
     // profiling
     bool profiling = false;
     struct Span { int cls; hipEvent_t a, b; };
@@ -268,6 +268,7 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
         m.tok_page = take((size_t)c.max_tokens * 4);
         m.bt_flat = take((size_t)c.max_seqs * c.max_blocks_per_seq * 4);
         m.dec_items = take((size_t)s->max_items * sizeof(DecodeItem));
+        m.dec_order = take((size_t)s->max_items * 4);
         m.dec_rows = take((size_t)c.max_seqs * sizeof(DecodeRow));
         m.pre_items = take((size_t)s->max_pre_items * sizeof(PrefillItem));
         m.total = off;
@@ -494,6 +495,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         ml.tok_page = take((size_t)T * 4);
         ml.bt_flat = take((size_t)total_pages * 4);
         ml.dec_items = take((size_t)cnt_items * sizeof(DecodeItem));
+        ml.dec_order = take((size_t)cnt_items * 4);
         ml.dec_rows = take((size_t)n_dec * sizeof(DecodeRow));
         ml.pre_items = take((size_t)cnt_pre * sizeof(PrefillItem));
         ml.total = off;
@@ -502,6 +504,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     int32_t* tok_page = (int32_t*)(st_base + ml.tok_page);
     int32_t* bt_flat = (int32_t*)(st_base + ml.bt_flat);
     DecodeItem* dec_items = (DecodeItem*)(st_base + ml.dec_items);
+    int32_t* dec_order = (int32_t*)(st_base + ml.dec_order);
     DecodeRow* dec_rows = (DecodeRow*)(st_base + ml.dec_rows);
     PrefillItem* pre_items = (PrefillItem*)(st_base + ml.pre_items);
     int n_items = 0, n_rows = 0, n_pre = 0;
@@ -518,8 +521,12 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         if (n == 1) {
             const int len = cl + 1;
             dec_rows[n_rows++] = DecodeRow{(int32_t)row, n_items, (int32_t)ceil_div(len, part), 0};
-            for (int k0 = 0; k0 < len; k0 += part)
-                dec_items[n_items++] = DecodeItem{(int32_t)row, (int32_t)bt_off, k0, std::min(k0 + part, len)};
+            // equal shares (whole 32-key blocks) rather than full partitions plus a short remainder
+            const int nparts = (int)ceil_div(len, part);
+            const int share = (int)ceil_div(ceil_div(len, nparts), 32) * 32;
+            for (int k0 = 0; k0 < len; k0 += share)
+                dec_items[n_items++] = DecodeItem{(int32_t)row, (int32_t)bt_off, k0, std::min(k0 + share, len)};
+            dec_rows[n_rows - 1].num_items = n_items - dec_rows[n_rows - 1].first_item;
         } else {
             for (int t0 = 0; t0 < n; t0 += s->pre_rows)
                 pre_items[n_pre++] = PrefillItem{(int32_t)(row + t0), std::min(s->pre_rows, n - t0), cl + t0,
@@ -528,6 +535,11 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         bt_off += pages;
         row += n;
     }
+    // launch order of the decode items: longest first, so that the last workgroups to start are the shortest
+    for (int i = 0; i < n_items; ++i) dec_order[i] = i;
+    std::stable_sort(dec_order, dec_order + n_items, [&](int32_t x, int32_t y) {
+        return dec_items[x].kv_end - dec_items[x].kv_begin > dec_items[y].kv_end - dec_items[y].kv_begin;
+    });
     hipStream_t st = (hipStream_t)stream_;
     HIP_TRY(s, hipMemcpyAsync(s->meta_dev, st_base, ml.total, hipMemcpyHostToDevice, st));
     HIP_TRY(s, hipEventRecord(s->staging_ev[slot], st));
@@ -537,6 +549,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     const int32_t* d_tok_page = (const int32_t*)(s->meta_dev + ml.tok_page);
     const int32_t* d_bt = (const int32_t*)(s->meta_dev + ml.bt_flat);
     const DecodeItem* d_items = (const DecodeItem*)(s->meta_dev + ml.dec_items);
+    const int32_t* d_order = (const int32_t*)(s->meta_dev + ml.dec_order);
     const DecodeRow* d_rows = (const DecodeRow*)(s->meta_dev + ml.dec_rows);
     const PrefillItem* d_pre = (const PrefillItem*)(s->meta_dev + ml.pre_items);
 
@@ -596,7 +609,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         if (n_items > 0) {
             {
                 ProfScope ps(s, st, PC_ATTN_DECODE);
-                HIP_TRY(s, launch_decode_attention(aa, d_items, n_items, s->part_o, s->part_ml, st));
+                HIP_TRY(s, launch_decode_attention(aa, d_items, d_order, n_items, s->part_o, s->part_ml, st));
             }
             ProfScope ps(s, st, PC_ATTN_MERGE);
             HIP_TRY(s, launch_decode_combine(aa, d_rows, n_rows, s->part_o, s->part_ml, st));

@@ -251,13 +251,14 @@ __device__ __forceinline__ void init_state(AttnState<D, NB>& st) {
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256, 2) void decode_attention_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
+                                                                const int32_t* __restrict__ order,
                                                                 float* __restrict__ part_o,
                                                                 float* __restrict__ part_ml) {
     __shared__ float lds_o[4][16][D + 4];
     __shared__ float lds_m[4][16], lds_l[4][16];
     // the KV heads of one item are neighbouring workgroups: they run at the same time and read
     // neighbouring 4 KiB pieces of the same pages
-    const int item_idx = blockIdx.x / a.n_kv;
+    const int item_idx = order[blockIdx.x / a.n_kv];
     const int kvh = blockIdx.x % a.n_kv;
     const DecodeItem it = items[item_idx];
     const int g = a.n_q / a.n_kv;
@@ -480,12 +481,12 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, c
 
 }  // namespace
 
-hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
-                                   float* part_ml, hipStream_t stream) {
+hipError_t launch_decode_attention(const AttnArgs& a, const DecodeItem* items, const int32_t* order, int num_items,
+                                   float* part_o, float* part_ml, hipStream_t stream) {
     if (num_items <= 0) return hipSuccess;
     dim3 grid(num_items * a.n_kv);
-    if (a.d == 128) decode_attention_kernel<128><<<grid, 256, 0, stream>>>(a, items, part_o, part_ml);
-    else if (a.d == 64) decode_attention_kernel<64><<<grid, 256, 0, stream>>>(a, items, part_o, part_ml);
+    if (a.d == 128) decode_attention_kernel<128><<<grid, 256, 0, stream>>>(a, items, order, part_o, part_ml);
+    else if (a.d == 64) decode_attention_kernel<64><<<grid, 256, 0, stream>>>(a, items, order, part_o, part_ml);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
