@@ -91,12 +91,14 @@ struct AttnArgs {
 };
 
 // Decode rows (one new token per sequence).  Work items split the keys of a row into
-// partitions; every item writes one partial per KV head, then a second kernel merges.
+// partitions; every item writes one partial per query head, then a second kernel merges the rows
+// that have more than one item (DecodeRow lists only those).
 struct DecodeItem {
     int32_t row;       // token row
     int32_t bt_off;    // offset of the sequence's first page id in bt_flat
     int32_t kv_begin;  // first key of this partition (multiple of 32)
     int32_t kv_end;    // one past the last key of this partition
+    int32_t single;    // 1: the row's only item; the kernel writes the normalised output itself
 };
 struct DecodeRow {
     int32_t row;        // token row

@@ -520,13 +520,15 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         }
         if (n == 1) {
             const int len = cl + 1;
-            dec_rows[n_rows++] = DecodeRow{(int32_t)row, n_items, (int32_t)ceil_div(len, part), 0};
             // equal shares (whole 32-key blocks) rather than full partitions plus a short remainder
             const int nparts = (int)ceil_div(len, part);
             const int share = (int)ceil_div(ceil_div(len, nparts), 32) * 32;
+            const int first = n_items;
             for (int k0 = 0; k0 < len; k0 += share)
-                dec_items[n_items++] = DecodeItem{(int32_t)row, (int32_t)bt_off, k0, std::min(k0 + share, len)};
-            dec_rows[n_rows - 1].num_items = n_items - dec_rows[n_rows - 1].first_item;
+                dec_items[n_items++] = DecodeItem{(int32_t)row, (int32_t)bt_off, k0, std::min(k0 + share, len), 0};
+            // a row with a single item is finished by the attention kernel; the others are merged afterwards
+            if (n_items - first == 1) dec_items[first].single = 1;
+            else dec_rows[n_rows++] = DecodeRow{(int32_t)row, first, n_items - first, 0};
         } else {
             for (int t0 = 0; t0 < n; t0 += s->pre_rows)
                 pre_items[n_pre++] = PrefillItem{(int32_t)(row + t0), std::min(s->pre_rows, n - t0), cl + t0,

@@ -316,6 +316,14 @@ __global__ __launch_bounds__(256, 2) void decode_attention_kernel(AttnArgs a, co
             for (int v = 0; v < 4; ++v) acc[v] += ov[v] * sc;
             ls += lds_l[w][j] * sc;
         }
+        if (it.single) {  // same arithmetic as the merge kernel applies to a row with one partial
+            const float inv = 1.0f / ls;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] *= inv;
+            *reinterpret_cast<bf16x4*>(a.out + (int64_t)it.row * a.ld_o + (kvh * g + j) * D + e) =
+                __builtin_convertvector(acc, bf16x4);
+            continue;
+        }
         const int64_t slot = ((int64_t)item_idx * a.n_q + kvh * g + j);
         *reinterpret_cast<f32x4*>(part_o + slot * D + e) = acc;
         if (e == 0) {
