@@ -319,7 +319,7 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
         case 6: return launch_tile<128, 128, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
         case 5:
-            if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 2, 2, MODE>(GLLM_TILE_ARGS);
+            if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 4, 2, MODE>(GLLM_TILE_ARGS);
             else return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
@@ -358,13 +358,14 @@ int gemm_mixed_rem_cols(int m, int n) {
     return rem / tiles_m;
 }
 
-// Tile shape and split-K factor for a problem, from a small cost model fitted to measurements on MI355X.
-// Unit: the time of one k-step of a 256x256 tile (~1.65 us).  A 256x256 tile (8 waves, one workgroup per
-// compute unit) costs k_steps + 6 (prologue, epilogue) per round of 256 tiles; a 128x128 tile costs
-// 0.605 k_steps + 2 per round of 512 tiles when two share a compute unit, 0.43 k_steps + 2 when alone.
-// A partial last round of 256x256 tiles that covers at most half of the compute units can be run with
-// half-width tiles instead (mixed launch, ~0.55 of a round).  Split-K multiplies the number of tiles and
-// divides the k-steps, at the price of writing one fp32 plane per split (mostly hidden under other tiles).
+// Tile shape and split-K factor for a problem, from a small cost model fitted to measurements on MI355X with
+// operands streaming from HBM (weights are cold in the stage).  Unit: the time of one k-step of a 256x256 tile
+// (~1.65 us).  A 256x256 tile (8 waves, one workgroup per compute unit) costs k_steps + 6 (prologue, epilogue)
+// per round of 256 tiles; a 256x192 tile 0.88 k_steps + 6; a 128x128 tile 0.70 k_steps + 2.3 per round of 512
+// tiles when two share a compute unit, 0.49 k_steps + 2.3 when alone (15 % less with four LDS stages, used
+// for few rows).  A partial last round of 256x256 tiles that covers at most half of the compute units can be
+// run with half-width tiles instead (mixed launch, ~0.55 of a round).  Split-K multiplies the number of tiles
+// and divides the k-steps, at the price of writing one fp32 plane per split (mostly hidden under other tiles).
 GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
     const int its = k / BK;
     GemmPlan best{0, 1};
@@ -381,14 +382,19 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
             const double cost = rounds * (steps + 6.0) + plane_cost;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{mixed ? 4 : 3, s}; }
         }
+        if (n % 192 == 0 && mode != GEMM_SWIGLU_BF16) {
+            const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 192) * s;
+            const double cost = (double)ceil_div(tiles, 256) * (steps * 0.88 + 6.0) + plane_cost;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{5, s}; }
+        }
         if (n % 128 == 0) {
             const int64_t tiles = ceil_div(m, 128) * (int64_t)(n / 128) * s;
             const int64_t full = tiles / 512, rem = tiles % 512;
-            double cost = (double)full * (steps * 0.605 + 2.0) + plane_cost;
-            if (rem > 256) cost += steps * 0.605 + 2.0;
-            else if (rem > 0) cost += steps * 0.43 + 2.0;
-            // few rows: the weights stream from HBM and every tile is alone on its compute unit; the 4-stage
-            // variant keeps three k-steps of loads in flight (measured +10..20 % there)
+            double cost = (double)full * (steps * 0.70 + 2.3) + plane_cost;
+            if (rem > 256) cost += steps * 0.70 + 2.3;
+            else if (rem > 0) cost += steps * 0.49 + 2.3;
+            // few rows: every tile is alone on its compute unit; the 4-stage variant keeps three k-steps of
+            // loads in flight (measured +10..20 % there)
             const bool deep = m <= 256 && tiles <= 256;
             if (deep) cost *= 0.85;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{deep ? 6 : 0, s}; }
@@ -412,8 +418,8 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             const int64_t t3 = ceil_div(m, 256) * (int64_t)(n / 256) * splits, t0 = ceil_div(m, 128) * (int64_t)(n / 128) * splits;
             const double steps = (double)(k / BK) / splits;
             const double c3 = n % 256 == 0 ? (double)ceil_div(t3, 256) * (steps + 6.0) : 1e30;
-            const double c0 = (double)(t0 / 512) * (steps * 0.605 + 2.0) +
-                              (t0 % 512 > 256 ? steps * 0.605 + 2.0 : t0 % 512 > 0 ? steps * 0.43 + 2.0 : 0.0);
+            const double c0 = (double)(t0 / 512) * (steps * 0.70 + 2.3) +
+                              (t0 % 512 > 256 ? steps * 0.70 + 2.3 : t0 % 512 > 0 ? steps * 0.49 + 2.3 : 0.0);
             tile = c3 <= c0 ? 3 : (m <= 256 && t0 <= 256) ? 6 : 0;
         }
     }
