@@ -364,18 +364,18 @@ __global__ void decode_combine_kernel(AttnArgs a, const DecodeRow* __restrict__ 
 // that all share the same K/V: every 32-key block is brought into LDS once (global_load_lds into a ring
 // of 4 stages, three blocks in flight while one is processed: a block is only ~0.5 us of work, far less
 // than the memory latency) and read by all 4 waves.
-// LDS holds the pages exactly as the pool does, so the fragment reads are the same contiguous patterns
-// as in the decode kernel.  Column group cb = 2*wave + c covers head (cb % HW) and query rows
+// LDS holds the K pages exactly as the pool does and the V pages with a bank swizzle (see issue_block), so the
+// fragment reads are the same patterns as in the decode kernel.  Column group cb = 2*wave + c covers head (cb % HW) and query rows
 // 16*(cb / HW) .. +15 of the item.
 // ------------------------------------------------------------------------------------------
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 template <int D, int HW>
-__global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
+__global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a, const PrefillItem* __restrict__ items) {
     constexpr int NB = 2;
     constexpr int PAGE_BYTES = D * kPage * 2;  // one (page, head) of K or of V
-    constexpr int NS = 4;                      // LDS stages
+    constexpr int NS = 3;                      // LDS stages
     constexpr int IPB = PAGE_BYTES / 1024;     // load instructions per wave and block
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NS][4][PAGE_BYTES];  // [stage][K0,K1,V0,V1]
     const int groups = a.n_q / HW;
@@ -407,7 +407,11 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, c
     const bf16_t* pool = (wave < 2) ? a.k_pool : a.v_pool;
     auto page_id = [&](int blk) -> int { return bt[min(blk * 2 + (wave & 1), last_page)]; };
     auto issue_block = [&](int64_t page, int stage) {
-        const char* src = reinterpret_cast<const char*>(pool + (page * a.n_kv + kvh) * (int64_t)(D * kPage)) + lane * 16;
+        // K pages are copied as they are.  V pages ([dim][16 slots], 32 bytes per dim) swap the two 16-byte halves
+        // of the dims whose bit 3 is set: the 16 dims that 16 lanes read together then sit in 16 different bank
+        // groups (as stored, dims d and d+8 would collide).  A lane picks the source piece for its LDS position.
+        const int src_lane = (wave < 2) ? lane : lane ^ ((lane >> 4) & 1);
+        const char* src = reinterpret_cast<const char*>(pool + (page * a.n_kv + kvh) * (int64_t)(D * kPage)) + src_lane * 16;
 #pragma unroll
         for (int i = 0; i < IPB; ++i)
             __builtin_amdgcn_global_load_lds((gptr_t)(src + i * 1024), (lptr_t)(&lds[stage][wave][i * 1024]), 16, 0, 0);
@@ -434,7 +438,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, c
             for (int p = 0; p < 2; ++p)
 #pragma unroll
                 for (int b = 0; b < D / 16; ++b)
-                    vf[p][b] = *reinterpret_cast<const u32x2*>(&lds[stage][2 + p][((16 * b + r) * kPage + 4 * G) * 2]);
+                    vf[p][b] = *reinterpret_cast<const u32x2*>(
+                        &lds[stage][2 + p][(16 * b + r) * 32 + (((G >> 1) ^ ((r >> 3) & 1)) * 16) + (G & 1) * 8]);
             if (MASKED) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
             return vf;
         });
@@ -446,9 +451,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attention_kernel(AttnArgs a, c
     int pid_next = page_id(NS - 1);  // page of block blk + NS - 1, fetched one iteration ahead
     auto ring_advance = [&](int blk) {
         // blocks blk+1 .. blk+NS-2 may still be in flight
-        if (NS == 4 && IPB == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (NS == 4 && IPB == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * IPB) : "memory");
         __syncthreads();  // block blk has landed; nobody reads stage (blk-1) % NS any more
         issue_block(pid_next, (blk + NS - 1) % NS);
         pid_next = page_id(blk + NS);

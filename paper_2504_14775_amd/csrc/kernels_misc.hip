@@ -115,50 +115,53 @@ __global__ __launch_bounds__(256) void pack_gate_up_kernel(const bf16_t* __restr
 //   V element (head h, dim e) -> ((page*n_kv + h)*d*16) + e*16 + slot
 __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
     const int t = blockIdx.x;
-    const int d = a.d, half = d / 2;
+    const int d = a.d, half = d / 2, hq = half / 4;  // a thread handles 4 consecutive pairs
     const int pos = a.tok_pos[t];
     const int64_t page = a.tok_page[t];
     const int slot = pos & (kPage - 1);
     const float* row = a.qkv + (int64_t)t * a.ld_qkv;
-    const f32x2* cs = reinterpret_cast<const f32x2*>(a.rope_cs) + (int64_t)pos * half;
-    const int q_pairs = a.n_q * half, k_pairs = a.n_kv * half;
+    const f32x4* cs = reinterpret_cast<const f32x4*>(a.rope_cs + (int64_t)pos * half * 2);
+    const int q_quads = a.n_q * hq, k_quads = a.n_kv * hq;
     const int k_col0 = a.n_q * d, v_col0 = k_col0 + a.n_kv * d;
-    for (int i = threadIdx.x; i < q_pairs + k_pairs; i += 256) {
-        const bool is_q = i < q_pairs;
-        const int ii = is_q ? i : i - q_pairs;
-        const int hd = ii / half, j = ii % half;
+    auto gather = [&](int col) {  // sum of the partial planes (+ bias) of 4 consecutive columns
+        f32x4 v = *reinterpret_cast<const f32x4*>(row + col);
+        for (int p = 1; p < a.planes; ++p) v += *reinterpret_cast<const f32x4*>(row + p * a.plane_stride + col);
+        if (a.bias) v += __builtin_convertvector(*reinterpret_cast<const bf16x4*>(a.bias + col), f32x4);
+        return v;
+    };
+    for (int i = threadIdx.x; i < q_quads + k_quads; i += 256) {
+        const bool is_q = i < q_quads;
+        const int ii = is_q ? i : i - q_quads;
+        const int hd = ii / hq, j = (ii % hq) * 4;
         const int col = (is_q ? 0 : k_col0) + hd * d + j;
-        float lo = row[col], hi = row[col + half];
-        for (int p = 1; p < a.planes; ++p) {
-            lo += row[p * a.plane_stride + col];
-            hi += row[p * a.plane_stride + col + half];
+        const f32x4 lo = gather(col), hi = gather(col + half);
+        const f32x4 c01 = cs[j / 2], c23 = cs[j / 2 + 1];  // (cos, sin) of pairs j, j+1 | j+2, j+3
+        const f32x4 co = {c01[0], c01[2], c23[0], c23[2]}, si = {c01[1], c01[3], c23[1], c23[3]};
+        f32x4 rlo, rhi;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            rlo[v] = lo[v] * co[v] - hi[v] * si[v];
+            rhi[v] = hi[v] * co[v] + lo[v] * si[v];
         }
-        if (a.bias) {
-            lo += (float)a.bias[col];
-            hi += (float)a.bias[col + half];
-        }
-        f32x2 c = cs[j];
-        float rlo = lo * c[0] - hi * c[1];
-        float rhi = hi * c[0] + lo * c[1];
+        const bf16x4 blo = __builtin_convertvector(rlo, bf16x4), bhi = __builtin_convertvector(rhi, bf16x4);
         if (is_q) {
             bf16_t* q = a.q_out + (int64_t)t * a.ld_q + hd * d;
-            q[j] = (bf16_t)rlo;
-            q[j + half] = (bf16_t)rhi;
+            *reinterpret_cast<bf16x4*>(q + j) = blo;
+            *reinterpret_cast<bf16x4*>(q + j + half) = bhi;
         } else {
             bf16_t* kb = a.k_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage);
-            int e0 = j, e1 = j + half;
-            kb[(e0 >> 3) * (kPage * 8) + slot * 8 + (e0 & 7)] = (bf16_t)rlo;
-            kb[(e1 >> 3) * (kPage * 8) + slot * 8 + (e1 & 7)] = (bf16_t)rhi;
+            const int e0 = j, e1 = j + half;  // multiples of 4: the 4 elements stay inside one group of 8
+            *reinterpret_cast<bf16x4*>(kb + (e0 >> 3) * (kPage * 8) + slot * 8 + (e0 & 7)) = blo;
+            *reinterpret_cast<bf16x4*>(kb + (e1 >> 3) * (kPage * 8) + slot * 8 + (e1 & 7)) = bhi;
         }
     }
-    const int v_elems = a.n_kv * d;
-    for (int i = threadIdx.x; i < v_elems; i += 256) {
-        const int hd = i / d, e = i % d;
-        float v = row[v_col0 + i];
-        for (int p = 1; p < a.planes; ++p) v += row[p * a.plane_stride + v_col0 + i];
-        if (a.bias) v += (float)a.bias[v_col0 + i];
-        bf16_t* vb = a.v_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage);
-        vb[e * kPage + slot] = (bf16_t)v;
+    const int v_quads = a.n_kv * d / 4;
+    for (int i = threadIdx.x; i < v_quads; i += 256) {
+        const int hd = (i * 4) / d, e = (i * 4) % d;
+        const bf16x4 v = __builtin_convertvector(gather(v_col0 + i * 4), bf16x4);
+        bf16_t* vb = a.v_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage) + e * kPage + slot;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) vb[u * kPage] = v[u];
     }
 }
 
