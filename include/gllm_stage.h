@@ -186,6 +186,12 @@ gllm_status gllm_op_gemm_bf16_splitk(const void* a, int64_t lda, const void* w, 
                                      int32_t m, int32_t n, int32_t k, int32_t tile, int32_t splits, int64_t plane_stride,
                                      void* stream);
 
+/* Host only (no device call): the tile id and split-K factor the library's cost model picks for a problem
+ * when gllm_op_gemm_bf16 is called with tile = -1 (splits stays 1 unless mode is 0; at most max_splits).
+ * tile, splits: HOST out.  The stage plans its QKV, O and down projections with max_splits = 8. */
+gllm_status gllm_op_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t mode, int32_t max_splits, int32_t* tile,
+                              int32_t* splits);
+
 /* h[t][j] = bf16(x[t][j] * rsqrt(mean_j x^2 + eps) * gamma[j]); x fp32 [rows][hidden]. */
 gllm_status gllm_op_rmsnorm(const float* x, const void* gamma_bf16, void* h_bf16, int32_t rows, int32_t hidden,
                             double eps, void* stream);

@@ -25,7 +25,7 @@ EXPORTS = [
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
     "gllm_stage_bind_kv_pool", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
-    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
+    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_gemm_plan", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
 ]
 
 
@@ -107,6 +107,8 @@ def load_library():
     lib.gllm_op_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
     lib.gllm_op_gemm_bf16_splitk.restype = i32
     lib.gllm_op_gemm_bf16_splitk.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, i64, vp]
+    lib.gllm_op_gemm_plan.restype = i32
+    lib.gllm_op_gemm_plan.argtypes = [i32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.gllm_op_rmsnorm.restype = i32
     lib.gllm_op_rmsnorm.argtypes = [vp, vp, vp, i32, i32, C.c_double, vp]
     lib.gllm_op_peak_mfma.restype = i32
@@ -234,6 +236,16 @@ def gllm_op_gemm_bf16_splitk(a, w, out_planes, m: int, n: int, k: int, tile: int
                                       _stream_ptr(stream))
     if st != GLLM_OK:
         raise GllmError(st, "gllm_op_gemm_bf16_splitk")
+
+
+def gllm_op_gemm_plan(m: int, n: int, k: int, mode: int, max_splits: int):
+    """(tile, splits) the library would use for this problem; host only."""
+    lib = load_library()
+    tile, splits = C.c_int32(-1), C.c_int32(0)
+    st = lib.gllm_op_gemm_plan(m, n, k, mode, max_splits, C.byref(tile), C.byref(splits))
+    if st != GLLM_OK:
+        raise GllmError(st, "gllm_op_gemm_plan")
+    return tile.value, splits.value
 
 
 def gllm_op_rmsnorm(x, gamma, h, eps: float, stream=None):

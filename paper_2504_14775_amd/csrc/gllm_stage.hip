@@ -659,6 +659,17 @@ gllm_status gllm_op_gemm_bf16_splitk(const void* a, int64_t lda, const void* w, 
     return e == hipSuccess ? GLLM_OK : (e == hipErrorInvalidValue ? GLLM_E_UNSUPPORTED : GLLM_E_HIP);
 }
 
+gllm_status gllm_op_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t mode, int32_t max_splits, int32_t* tile,
+                              int32_t* splits) {
+    if (!tile || !splits || m < 1 || n < 1 || k < 1 || n % 64 != 0 || k % 64 != 0 || max_splits < 1 || mode < 0 ||
+        mode > GEMM_SWIGLU_BF16)
+        return GLLM_E_INVALID;
+    const GemmPlan p = gemm_plan(m, n, k, mode, max_splits);
+    *tile = p.tile;
+    *splits = p.splits;
+    return GLLM_OK;
+}
+
 gllm_status gllm_op_rmsnorm(const float* x, const void* gamma, void* h, int32_t rows, int32_t hidden, double eps,
                             void* stream) {
     if (!x || !gamma || !h || hidden % 4 != 0) return GLLM_E_INVALID;

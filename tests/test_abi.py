@@ -57,3 +57,33 @@ def test_create_rejects_bad_configs_before_touching_a_device():
     with pytest.raises(B.GllmError) as e:
         B.Stage(cfg)
     assert e.value.status == -1
+
+
+def test_gemm_planner_choices_are_launchable():
+    """Host logic of the tile / split-K planner: whatever it picks must satisfy the launch rules of that tile
+    (column multiple, split divides the 64-wide k-steps, splits only in store mode), for the stage shapes and a
+    sweep of ragged row counts."""
+    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128}
+    seen = set()
+    for shape in synth.SHAPES.values():
+        H, I = shape.hidden, shape.intermediate
+        pad = lambda v, q: (v + q - 1) // q * q
+        n_qkv = pad((shape.n_q_heads + 2 * shape.n_kv_heads) * shape.head_dim, 256)
+        problems = [(n_qkv, pad(H, 64), 0), (pad(H, 256), pad(shape.n_q_heads * shape.head_dim, 64), 0),
+                    (2 * pad(I, 256), pad(H, 64), 2), (pad(H, 256), pad(I, 256), 0)]
+        for m in (1, 17, 128, 256, 257, 512, 1000, 2048, 2560, 4160):
+            for n, k, mode in problems:
+                tile, splits = B.gllm_op_gemm_plan(m, n, k, mode, 8)
+                seen.add(tile)
+                assert tile in col_multiple and n % col_multiple[tile] == 0, (shape.name, m, n, k, mode, tile)
+                assert 1 <= splits <= 8 and (k // 64) % splits == 0
+                if mode != 0:
+                    assert splits == 1 and tile != 5
+                if tile == 4:
+                    tiles = ((m + 255) // 256) * (n // 256)
+                    assert splits == 1 and tiles >= 256 and 0 < tiles % 256 <= 128
+                assert B.gllm_op_gemm_plan(m, n, k, mode, 8) == (tile, splits)          # deterministic
+                assert B.gllm_op_gemm_plan(m, n, k, mode, 1)[1] == 1                    # the cap is respected
+    assert {3, 6}.issubset(seen)         # big problems get the 256x256 tile, few rows the deep 128x128 one
+    with pytest.raises(B.GllmError):
+        B.gllm_op_gemm_plan(128, 100, 4096, 0, 8)

@@ -163,6 +163,29 @@ def test_mid_shape_multi_layer_ragged_batch():
     check_pool("V", r["gv"], vp0, r["vp"], MID.num_layers, mask=mv)
 
 
+@pytest.mark.parametrize("min_wgs", [1, 64, 10 ** 6])
+def test_decode_rows_whole_or_partitioned_match_the_oracle(min_wgs):
+    """decode_min_workgroups = 1 leaves every decode row whole (finished by the attention kernel itself);
+    10^6 cuts rows down to the smallest partition (256 keys) and sends them through the merge kernel; 64 mixes
+    both in one batch.  All three must meet the oracle and agree with each other to fp32 rounding."""
+    print(f"decode partitioning, decode_min_workgroups={min_wgs}", flush=True)
+    one_layer = dataclasses.replace(MID, num_layers=1, name="mid1")
+    seqs = [(1, 0), (1, 31), (1, 32), (1, 255), (1, 256), (1, 257), (1, 511), (1, 512), (1, 700), (1, 1023),
+            (1, 1500), (40, 9)]
+    batch = synth.build_batch(seqs, 11, spare_blocks=5, label="dec")
+    w = layer_weights_np(one_layer, 11)
+    kp0, vp0 = pool_np(one_layer, 11, batch.num_blocks)
+    x = hidden_np(one_layer, 11, batch.num_tokens)
+    stage = GpuStage(one_layer, w, [batch])
+    stage.stage.set_option("decode_min_workgroups", min_wgs)
+    r = run_both(one_layer, w, batch, kp0, vp0, x, stage=stage)
+    assert_output(f"dec{min_wgs}", r, literal=False)
+    base = GpuStage(one_layer, w, [batch])
+    _, base32 = base.run(batch, to_dev_bits(kp0), to_dev_bits(vp0), to_dev_bits(x))
+    rms = float(np.sqrt((r["ref"] ** 2).mean()))
+    assert np.abs(r["out32"] - base32.cpu().numpy()).max() <= 1e-3 * max(1.0, rms)
+
+
 def test_qkv_bias_and_nan_sentinels_in_unused_slots():
     print("qkv bias + NaN sentinel in never-written slots", flush=True)
     shape = dataclasses.replace(synth.SHAPES["tiny"], has_qkv_bias=True, name="tiny_bias")
