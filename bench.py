@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # plain 1 GiB copy (profiles/stage_llama3_8b_pp4_hbm_traffic.txt): mean over the GEMM launches of a step,
 # and the decode attention kernel.  Measured offline (counters cannot be read from inside the process).
 MEASURED_TRAFFIC_BYTES = {
-    "llama3_8b_pp4": {"gemm": 497.8e6, "decode_attention": 2467.0e6 + 21.5e6},
+    "llama3_8b_pp4": {"gemm": 476.4e6, "decode_attention": 2467.1e6 + 2.1e6},
 }
 
 
