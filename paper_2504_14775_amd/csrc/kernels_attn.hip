@@ -20,6 +20,7 @@
 #include "common.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace {
 
@@ -28,7 +29,7 @@ constexpr float kNegBig = -1.0e30f;
 template <int D>
 struct KvFrag {
     u32x4 k[2][D / 32];  // [page][k-step]
-    u32x2 v[2][D / 16];  // [page][16-dim block]
+    u32x4 v[D / 16];     // [16-dim block]: elements 0,1 = 4 keys of page 0, elements 2,3 = 4 keys of page 1
 };
 
 template <int D>
@@ -44,7 +45,11 @@ __device__ __forceinline__ void load_kv(KvFrag<D>& f, const bf16_t* __restrict__
 #pragma unroll
         for (int s = 0; s < D / 32; ++s) f.k[p][s] = *reinterpret_cast<const u32x4*>(kb + s * 512);
 #pragma unroll
-        for (int b = 0; b < D / 16; ++b) f.v[p][b] = *reinterpret_cast<const u32x2*>(vb + b * 256);
+        for (int b = 0; b < D / 16; ++b) {
+            const u32x2 t = *reinterpret_cast<const u32x2*>(vb + b * 256);
+            f.v[b][2 * p] = t[0];
+            f.v[b][2 * p + 1] = t[1];
+        }
     }
 }
 
@@ -57,9 +62,9 @@ struct AttnState {
 };
 
 // Masks the V fragments of keys >= valid_end (slots that hold no data yet may contain any bit pattern,
-// also NaN, and 0 * NaN would poison the P.V product).  v[p][b] holds 4 keys of page p, dims block b.
+// also NaN, and 0 * NaN would poison the P.V product).  v[b] holds 4 keys of page 0 and 4 of page 1, dims block b.
 template <int D>
-__device__ __forceinline__ void mask_unwritten_v(u32x2 (&v)[2][D / 16], int tb, int valid_end, int lane) {
+__device__ __forceinline__ void mask_unwritten_v(u32x4 (&v)[D / 16], int tb, int valid_end, int lane) {
     const int G = lane >> 4;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -69,8 +74,8 @@ __device__ __forceinline__ void mask_unwritten_v(u32x2 (&v)[2][D / 16], int tb, 
         const uint32_t m1 = nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0x0000FFFFu : 0u);
 #pragma unroll
         for (int b = 0; b < D / 16; ++b) {
-            v[p][b][0] &= m0;
-            v[p][b][1] &= m1;
+            v[b][2 * p] &= m0;
+            v[b][2 * p + 1] &= m1;
         }
     }
 }
@@ -109,22 +114,21 @@ __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2]
 //
 // m is the reference exponent of a column (identical in the four lanes that share the column); p =
 // 2^(s*c - m) with c = log2(e)/sqrt(d).  Softmax does not care which reference is used as long as nothing
-// overflows, so the block's own maximum is NOT awaited: p is formed against the reference left by the
-// earlier blocks while the block maximum travels across the lanes (two LDS-crossbar permutes per group,
-// ~150 cycles each) under the exponentials and MFMAs; only afterwards, if it exceeded the reference, are m,
-// l and the accumulators moved to it.  The exact order (reduce, move, exponentiate) is taken when some lane
-// sees a score more than 64 above its reference -- always in a wave's first block, where the reference
-// is still the huge negative start value -- so p stays below 2^64 and sums of 2^13 of them stay finite.
-// The code is straight-line except for those two rare wave-uniform branches, and all groups advance
-// together, so the scheduler can overlap the groups' dependency chains.  DEFER = false gives the plain
-// exact order (reference moved before the exponentials whenever a lane's maximum exceeds it): the
-// memory-bound decode kernel, with one group per wave, gains nothing from deferring and saves registers.
+// overflows.  DEFER = true lets the reference lag: it is only moved (to the exact running maximum: two
+// cross-lane exchanges per group, then m, l and the accumulators are rescaled) when some lane sees a score
+// more than 64 above it -- always in a wave's first block, where the reference is still the huge negative
+// start value, and practically never afterwards -- so p stays below 2^64, sums of 2^13 of them stay finite,
+// and the common path has no cross-lane traffic and no rescaling at all: a lane-local maximum, one wave vote,
+// the exponentials, the MFMAs.  DEFER = false moves the reference whenever a lane's maximum exceeds it (the
+// textbook order): the memory-bound decode kernel, with one group per wave, gains nothing from deferring.
 constexpr float kRefSlack = 64.0f;
 
-template <int D, int NB, bool DEFER, typename GetV>
+// issue_v() is called before the exponentials (a caller that fetches V from LDS starts its reads there),
+// get_v() after them (it returns the fragments, waiting for them if need be).
+template <int D, int NB, bool DEFER, typename IssueV, typename GetV>
 __device__ __forceinline__ void update_groups(AttnState<D, NB>& st, const float (&sc)[NB][8], float scale_log2,
-                                              GetV&& get_v) {
-    float lm[NB], bm[NB];
+                                              IssueV&& issue_v, GetV&& get_v) {
+    float lm[NB];
     bool low = false;
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
@@ -134,14 +138,12 @@ __device__ __forceinline__ void update_groups(AttnState<D, NB>& st, const float 
         lm[c] = x * scale_log2;
         low |= DEFER ? lm[c] > st.m[c] + kRefSlack : lm[c] > st.m[c];
     }
-#pragma unroll
-    for (int c = 0; c < NB; ++c) bm[c] = fmaxf(lm[c], __shfl_xor(lm[c], 16));
-#pragma unroll
-    for (int c = 0; c < NB; ++c) bm[c] = fmaxf(bm[c], __shfl_xor(bm[c], 32));
-    auto move_references = [&]() {
+    if (__any(low)) {  // wave-uniform
 #pragma unroll
         for (int c = 0; c < NB; ++c) {
-            const float m_new = fmaxf(st.m[c], bm[c]);
+            float bm = fmaxf(lm[c], __shfl_xor(lm[c], 16));
+            bm = fmaxf(bm, __shfl_xor(bm, 32));
+            const float m_new = fmaxf(st.m[c], bm);
             const float alpha = __builtin_amdgcn_exp2f(st.m[c] - m_new);
             st.l[c] *= alpha;
 #pragma unroll
@@ -150,8 +152,8 @@ __device__ __forceinline__ void update_groups(AttnState<D, NB>& st, const float 
                 for (int v = 0; v < 4; ++v) st.o[c][b][v] *= alpha;
             st.m[c] = m_new;
         }
-    };
-    if (__any(low)) move_references();  // exact order: waits for the block maxima
+    }
+    issue_v();
     bf16x8 pb[NB];
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
@@ -165,20 +167,12 @@ __device__ __forceinline__ void update_groups(AttnState<D, NB>& st, const float 
         st.l[c] += psum;
         pb[c] = __builtin_convertvector(p, bf16x8);
     }
-    const u32x2 (&vf)[2][D / 16] = get_v();
+    const u32x4 (&vf)[D / 16] = get_v();
 #pragma unroll
-    for (int b = 0; b < D / 16; ++b) {
-        const u32x4 vv = {vf[0][b][0], vf[0][b][1], vf[1][b][0], vf[1][b][1]};
+    for (int b = 0; b < D / 16; ++b)
 #pragma unroll
         for (int c = 0; c < NB; ++c)
-            st.o[c][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pb[c], st.o[c][b], 0, 0, 0);
-    }
-    if (DEFER) {
-        bool moved = false;
-#pragma unroll
-        for (int c = 0; c < NB; ++c) moved |= bm[c] > st.m[c];
-        if (__any(moved)) move_references();  // deferred: the next block starts from the new references
-    }
+            st.o[c][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[b]), pb[c], st.o[c][b], 0, 0, 0);
 }
 
 // One block of 32 keys for NB column groups, K/V fragments in registers.
@@ -193,7 +187,7 @@ __device__ __forceinline__ void attend_block(AttnState<D, NB>& st, KvFrag<D>& f,
     float sc[NB][8];
 #pragma unroll
     for (int c = 0; c < NB; ++c) score_group<D>(sc[c], f.k, qf[c], tb, limit[c], need_mask, lane);
-    update_groups<D, NB, false>(st, sc, scale_log2, [&]() -> const u32x2 (&)[2][D / 16] { return f.v; });
+    update_groups<D, NB, false>(st, sc, scale_log2, []() {}, [&]() -> const u32x4 (&)[D / 16] { return f.v; });
 }
 
 // Walks key blocks [blk_begin, blk_end) (units of 32 keys) of one sequence.  Page ids are fetched 64
@@ -358,6 +352,27 @@ __global__ void decode_combine_kernel(AttnArgs a, const DecodeRow* __restrict__ 
     *reinterpret_cast<bf16x4*>(a.out + (int64_t)rw.row * a.ld_o + hq * D + e) = __builtin_convertvector(acc, bf16x4);
 }
 
+// Two 8-byte LDS reads at addr + 512*B and addr + 512*(B + GAP) into one 4-register tuple (ds_read2st64_b64).
+// Written as assembly because the compiler pairs neighbouring dims blocks instead and then needs 3 register
+// moves per operand to regroup them.  The result is valid only after await_lds().
+template <int B, int GAP>
+__device__ __forceinline__ void read_v_operand(u32x4& v, uint32_t addr) {
+    asm volatile("ds_read2st64_b64 %0, %1 offset0:%2 offset1:%3" : "=v"(v) : "v"(addr), "n"(B), "n"(B + GAP) : "memory");
+}
+template <int GAP, int N, int... Bs>
+__device__ __forceinline__ void read_v_operands(u32x4 (&v)[N], uint32_t addr, std::integer_sequence<int, Bs...>) {
+    (read_v_operand<Bs, GAP>(v[Bs], addr), ...);
+}
+// Waits for all outstanding LDS reads; the registers are passed through the statement so that no use of them
+// can be scheduled before it.
+template <int N>
+__device__ __forceinline__ void await_lds(u32x4 (&v)[N]) {
+    static_assert(N % 4 == 0, "fragments are awaited four at a time");
+#pragma unroll
+    for (int b = 0; b < N; b += 4)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[b]), "+v"(v[b + 1]), "+v"(v[b + 2]), "+v"(v[b + 3])::"memory");
+}
+
 // ------------------------------------------------------------------------------------------
 // Prefill: one workgroup of 4 waves per (item, group of HW query heads of one KV head).  An item is up
 // to 128/HW consecutive query rows of a chunk, so the workgroup owns 8 column groups of 16 (2 per wave)
@@ -432,17 +447,22 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a, c
 #pragma unroll
             for (int c = 0; c < NB; ++c) score_group<D>(sc[c], kf, qf[c], tb, limit[c], MASKED, lane);
         }
-        u32x2 vf[2][D / 16];
-        update_groups<D, NB, true>(st, sc, a.scale_log2, [&]() -> const u32x2 (&)[2][D / 16] {
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int b = 0; b < D / 16; ++b)
-                    vf[p][b] = *reinterpret_cast<const u32x2*>(
-                        &lds[stage][2 + p][(16 * b + r) * 32 + (((G >> 1) ^ ((r >> 3) & 1)) * 16) + (G & 1) * 8]);
-            if (MASKED) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
-            return vf;
-        });
+        // V^T operands: dims block b needs 4 keys of page 0 and 4 keys of page 1 in one 4-register operand.  One
+        // two-address LDS read (addresses PAGE_BYTES apart) delivers exactly that; the reads are issued before the
+        // exponentials and awaited after them.
+        u32x4 vf[D / 16];
+        update_groups<D, NB, true>(
+            st, sc, a.scale_log2,
+            [&]() {
+                const uint32_t addr = (uint32_t)(uintptr_t)(
+                    &lds[stage][2][r * 32 + (((G >> 1) ^ ((r >> 3) & 1)) * 16) + (G & 1) * 8]);
+                read_v_operands<PAGE_BYTES / 512>(vf, addr, std::make_integer_sequence<int, D / 16>{});
+            },
+            [&]() -> const u32x4 (&)[D / 16] {
+                await_lds(vf);
+                if (MASKED) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
+                return vf;
+            });
     };
     // every wave always issues its piece (indices past the end re-read the last page into a stage nobody
     // reads), so the count of outstanding loads is the same in every iteration
