@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgllm_stage.so")
 BUILD_DIR = os.path.join(HERE, "_build")
-SOURCES = ["gllm_stage.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_misc.hip", "kernels_peak.hip"]
+SOURCES = ["gllm_stage.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_misc.hip", "kernels_peak.hip",
+           "gllm_sched.cpp"]   # the last one is host code only (the micro-batch scheduler)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -28,7 +29,8 @@ def hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    flags = FLAGS if src.endswith(".hip") else ["-O2", "-std=c++17", "-fPIC", "-Wall"]
+    cmd = [hipcc(), *flags, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
