@@ -1,0 +1,359 @@
+// First / last pipeline-stage extras (arxiv 2504.14775, section 2.1): embedding layer, projection of the final
+// hidden states to logits, sampling strategy.  Contract of every entry point: include/gllm_head.h.
+#include "../../include/gllm_head.h"
+#include "common.h"
+
+#include <climits>
+#include <string>
+
+namespace {
+
+// ---- embedding: one workgroup per token row, 16-byte pieces -----------------------------------------------
+__global__ __launch_bounds__(256) void embedding_kernel(const int32_t* __restrict__ ids, const bf16_t* __restrict__ table,
+                                                        bf16_t* __restrict__ out, int hidden, int vocab, int64_t ld_out) {
+    const int t = blockIdx.x;
+    const int id = ids[t];
+    const bool known = id >= 0 && id < vocab;
+    const u32x4* src = reinterpret_cast<const u32x4*>(table + (int64_t)(known ? id : 0) * hidden);
+    u32x4* dst = reinterpret_cast<u32x4*>(out + (int64_t)t * ld_out);
+    if (known) {
+        for (int i = threadIdx.x; i < hidden / 8; i += 256) dst[i] = src[i];
+    } else {
+        for (int i = threadIdx.x; i < hidden / 8; i += 256) dst[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+// ---- final norm of selected rows: h[i] = bf16(x[rows[i]] * rsqrt(mean x^2 + eps) * gain) --------------------
+__global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const float* __restrict__ x, int num_x_rows,
+                                                             const int32_t* __restrict__ rows,
+                                                             const bf16_t* __restrict__ gain, bf16_t* __restrict__ h,
+                                                             int hidden, float eps) {
+    __shared__ float part[4];
+    const int r = min(max(rows[blockIdx.x], 0), num_x_rows - 1);
+    const f32x4* src = reinterpret_cast<const f32x4*>(x + (int64_t)r * hidden);
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < hidden / 4; i += 256) {
+        const f32x4 v = src[i];
+        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float rstd = rsqrtf((part[0] + part[1] + part[2] + part[3]) / (float)hidden + eps);
+    bf16_t* dst = h + (int64_t)blockIdx.x * hidden;
+    for (int i = threadIdx.x; i < hidden / 4; i += 256) {
+        const f32x4 v = src[i];
+        const f32x4 g = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(gain + i * 4), f32x4);
+        f32x4 y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = v[e] * rstd * g[e];
+        *reinterpret_cast<bf16x4*>(dst + i * 4) = __builtin_convertvector(y, bf16x4);
+    }
+}
+
+// rows of w [vocab][hidden] -> padded [vocab_pad][hidden], zero rows past vocab
+__global__ __launch_bounds__(256) void pad_rows_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ out, int vocab,
+                                                       int hidden) {
+    const int v = blockIdx.x;
+    const u32x4* src = reinterpret_cast<const u32x4*>(w + (int64_t)v * hidden);
+    u32x4* dst = reinterpret_cast<u32x4*>(out + (int64_t)v * hidden);
+    if (v < vocab) {
+        for (int i = threadIdx.x; i < hidden / 8; i += 256) dst[i] = src[i];
+    } else {
+        for (int i = threadIdx.x; i < hidden / 8; i += 256) dst[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+// ---- sampling: one workgroup per row ----------------------------------------------------------------------
+constexpr int kSampleThreads = 1024;
+
+// order-preserving map from float to unsigned: a < b  <=>  key(a) < key(b) (for non-NaN values)
+__device__ __forceinline__ uint32_t float_key(float f) {
+    const uint32_t b = __float_as_uint(f);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+// Sum over the workgroup, the same association for every call: thread-local values are combined by a fixed tree.
+__device__ __forceinline__ float block_sum(float v, float* scratch) {
+    const int tid = threadIdx.x;
+    scratch[tid] = v;
+    __syncthreads();
+    for (int s = kSampleThreads / 2; s > 0; s >>= 1) {
+        if (tid < s) scratch[tid] += scratch[tid + s];
+        __syncthreads();
+    }
+    const float r = scratch[0];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __restrict__ logits, int64_t ld, int vocab,
+                                                                const float* __restrict__ temperature,
+                                                                const int32_t* __restrict__ top_k,
+                                                                const float* __restrict__ top_p,
+                                                                const float* __restrict__ uniform,
+                                                                int32_t* __restrict__ out) {
+    __shared__ float fs[kSampleThreads];
+    __shared__ int is[kSampleThreads];
+    __shared__ unsigned hist[256];
+    __shared__ uint32_t sh_key;
+    __shared__ int sh_int;
+    const int tid = threadIdx.x, row = blockIdx.x;
+    const float* lg = logits + (int64_t)row * ld;
+
+    // the largest logit and its lowest index (greedy; also the softmax reference)
+    float best = -INFINITY;
+    int best_i = INT_MAX;
+    for (int i = tid; i < vocab; i += kSampleThreads) {
+        const float v = lg[i];
+        if (v > best) {
+            best = v;
+            best_i = i;
+        }
+    }
+    fs[tid] = best;
+    is[tid] = best_i;
+    __syncthreads();
+    for (int s = kSampleThreads / 2; s > 0; s >>= 1) {
+        if (tid < s) {
+            const float ov = fs[tid + s];
+            const int oi = is[tid + s];
+            if (ov > fs[tid] || (ov == fs[tid] && oi < is[tid])) {
+                fs[tid] = ov;
+                is[tid] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    best = fs[0];
+    best_i = is[0] == INT_MAX ? 0 : is[0];
+    __syncthreads();
+    const float temp = temperature[row];
+    if (!(temp > 0.f)) {
+        if (tid == 0) out[row] = best_i;
+        return;
+    }
+    const float zmax = best / temp;
+
+    // top-k: the k-th largest key by a radix select over the four bytes of the key, most significant first
+    uint32_t floor_key = 0;  // tokens with key >= floor_key are kept
+    const int k = top_k[row];
+    if (k > 0 && k < vocab) {
+        uint32_t prefix = 0;
+        int want = k;
+        for (int byte = 3; byte >= 0; --byte) {
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const int shift = byte * 8;
+            const uint32_t high_mask = byte == 3 ? 0u : 0xFFFFFFFFu << (shift + 8);
+            for (int i = tid; i < vocab; i += kSampleThreads) {
+                const uint32_t key = float_key(lg[i] / temp);
+                if ((key & high_mask) == (prefix & high_mask)) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int bin = 255, above = 0;
+                while (bin > 0 && above + (int)hist[bin] < want) above += (int)hist[bin--];
+                sh_key = prefix | ((uint32_t)bin << shift);
+                sh_int = want - above;
+            }
+            __syncthreads();
+            prefix = sh_key;
+            want = sh_int;
+            __syncthreads();
+        }
+        floor_key = prefix;
+    }
+
+    auto mass_from = [&](uint32_t from) {  // sum of exp(z - zmax) over the tokens with key >= from
+        float s = 0.f;
+        for (int i = tid; i < vocab; i += kSampleThreads) {
+            const float z = lg[i] / temp;
+            if (float_key(z) >= from) s += __expf(z - zmax);
+        }
+        return block_sum(s, fs);
+    };
+    float total = mass_from(floor_key);
+
+    // nucleus: the largest key t with mass(key >= t) >= top_p * total, by bisection over the key space
+    const float p = top_p[row];
+    if (p < 1.f) {
+        const float need = p * total;
+        uint32_t lo = floor_key, hi = float_key(zmax);  // mass(>= lo) >= need holds; the answer is at most key(zmax)
+        // invariant: mass(>= lo) >= need, and mass(>= hi + 1) < need
+        while (lo < hi) {
+            const uint32_t mid = lo + (hi - lo + 1) / 2;
+            if (mass_from(mid) >= need) lo = mid;
+            else hi = mid - 1;
+        }
+        floor_key = lo;
+        total = mass_from(floor_key);
+    }
+
+    // draw in index order: every thread owns a run of consecutive tokens
+    const float target = uniform[row] * total;
+    const int run = (vocab + kSampleThreads - 1) / kSampleThreads;
+    const int i0 = min(tid * run, vocab), i1 = min(i0 + run, vocab);
+    float own = 0.f;
+    int last_kept = -1;
+    for (int i = i0; i < i1; ++i) {
+        const float z = lg[i] / temp;
+        if (float_key(z) >= floor_key) {
+            own += __expf(z - zmax);
+            last_kept = i;
+        }
+    }
+    fs[tid] = own;
+    is[tid] = last_kept;
+    __syncthreads();
+    if (tid == 0) {  // serial prefix over 1024 partial sums: fixed order, negligible next to the passes above
+        float before = 0.f;
+        int winner = -1, last = -1;
+        for (int t = 0; t < kSampleThreads; ++t) {
+            const float v = fs[t];
+            if (winner < 0 && before + v > target) {
+                winner = t;
+                sh_key = __float_as_uint(before);
+            }
+            before += v;
+            if (is[t] >= 0) last = is[t];
+        }
+        sh_int = winner;
+        if (winner < 0) out[row] = last < 0 ? best_i : last;  // u * total rounded up to the total: the last kept token
+    }
+    __syncthreads();
+    if (tid == sh_int) {
+        float running = __uint_as_float(sh_key);
+        int pick = last_kept;
+        for (int i = i0; i < i1; ++i) {
+            const float z = lg[i] / temp;
+            if (float_key(z) >= floor_key) {
+                running += __expf(z - zmax);
+                if (running > target) {
+                    pick = i;
+                    break;
+                }
+            }
+        }
+        out[row] = pick;
+    }
+}
+
+}  // namespace
+
+struct gllm_head {
+    gllm_head_config cfg;
+    int32_t vocab_pad = 0;
+    bf16_t* w = nullptr;      // [vocab_pad][hidden]
+    bf16_t* gain = nullptr;   // [hidden]
+    bf16_t* h = nullptr;      // workspace: [round_up(max_rows, 256)][hidden]
+    bool loaded = false;
+    std::string err;
+};
+
+namespace {
+gllm_status fail(gllm_head* s, gllm_status st, const std::string& msg) {
+    if (s) s->err = msg;
+    return st;
+}
+}  // namespace
+
+extern "C" {
+
+gllm_status gllm_op_embedding(const int32_t* ids, const void* table, void* out, int32_t num_tokens, int32_t hidden,
+                              int32_t vocab, int64_t ld_out, void* stream) {
+    if (!ids || !table || !out || num_tokens < 0 || hidden < 8 || hidden % 8 != 0 || vocab < 1 || ld_out < hidden ||
+        ld_out % 8 != 0)
+        return GLLM_E_INVALID;
+    if (num_tokens == 0) return GLLM_OK;
+    embedding_kernel<<<num_tokens, 256, 0, (hipStream_t)stream>>>(ids, (const bf16_t*)table, (bf16_t*)out, hidden, vocab, ld_out);
+    return hipGetLastError() == hipSuccess ? GLLM_OK : GLLM_E_HIP;
+}
+
+gllm_status gllm_head_create(const gllm_head_config* cfg, gllm_head** out) {
+    if (!out) return GLLM_E_INVALID;
+    *out = nullptr;
+    if (!cfg || cfg->hidden < 64 || cfg->hidden % 64 != 0 || cfg->vocab < 1 || cfg->vocab > (1 << 24) || cfg->max_rows < 1 ||
+        !(cfg->rms_eps >= 0.0))
+        return GLLM_E_INVALID;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n < 1) return GLLM_E_HIP;
+    gllm_head* s = new gllm_head();
+    s->cfg = *cfg;
+    s->vocab_pad = (int32_t)round_up(cfg->vocab, 256);
+    if (hipMalloc((void**)&s->w, (size_t)s->vocab_pad * cfg->hidden * 2) != hipSuccess ||
+        hipMalloc((void**)&s->gain, (size_t)cfg->hidden * 2) != hipSuccess) {
+        if (s->w) (void)hipFree(s->w);
+        delete s;
+        return GLLM_E_HIP;
+    }
+    *out = s;
+    return GLLM_OK;
+}
+
+void gllm_head_destroy(gllm_head* s) {
+    if (!s) return;
+    (void)hipFree(s->w);
+    (void)hipFree(s->gain);
+    delete s;
+}
+
+const char* gllm_head_last_error(const gllm_head* s) { return s ? s->err.c_str() : "null head"; }
+
+size_t gllm_head_workspace_bytes(const gllm_head* s) {
+    return s ? (size_t)round_up(s->cfg.max_rows, 256) * s->cfg.hidden * 2 : 0;
+}
+
+gllm_status gllm_head_bind_workspace(gllm_head* s, void* workspace, size_t bytes) {
+    if (!s || !workspace) return GLLM_E_INVALID;
+    if (bytes < gllm_head_workspace_bytes(s)) return fail(s, GLLM_E_CAPACITY, "workspace too small");
+    if ((uintptr_t)workspace % 256 != 0) return fail(s, GLLM_E_INVALID, "workspace must be 256-byte aligned");
+    s->h = (bf16_t*)workspace;
+    return GLLM_OK;
+}
+
+gllm_status gllm_head_load(gllm_head* s, const void* norm_gain, const void* w_vocab, void* stream) {
+    if (!s || !norm_gain || !w_vocab) return GLLM_E_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(s->gain, norm_gain, (size_t)s->cfg.hidden * 2, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(s, GLLM_E_HIP, "copy of the norm gain failed");
+    pad_rows_kernel<<<s->vocab_pad, 256, 0, st>>>((const bf16_t*)w_vocab, s->w, s->cfg.vocab, s->cfg.hidden);
+    if (hipGetLastError() != hipSuccess) return fail(s, GLLM_E_HIP, "weight repack launch failed");
+    s->loaded = true;
+    return GLLM_OK;
+}
+
+int32_t gllm_head_padded_vocab(const gllm_head* s) { return s ? s->vocab_pad : 0; }
+
+gllm_status gllm_head_logits(gllm_head* s, const float* x, int32_t num_x_rows, const int32_t* rows, int32_t num_rows,
+                             float* logits, int64_t ld_logits, void* stream) {
+    if (!s || !x || !rows || !logits || num_x_rows < 1 || num_rows < 0) return GLLM_E_INVALID;
+    if (!s->loaded || !s->h) return fail(s, GLLM_E_STATE, "load the weights and bind the workspace first");
+    if (num_rows > s->cfg.max_rows) return fail(s, GLLM_E_CAPACITY, "more rows than max_rows");
+    if (ld_logits < s->vocab_pad || ld_logits % 4 != 0) return fail(s, GLLM_E_INVALID, "ld_logits must cover the padded vocabulary");
+    if (num_rows == 0) return GLLM_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int H = s->cfg.hidden;
+    gather_rmsnorm_kernel<<<num_rows, 256, 0, st>>>(x, num_x_rows, rows, s->gain, s->h, H, (float)s->cfg.rms_eps);
+    if (hipGetLastError() != hipSuccess) return fail(s, GLLM_E_HIP, "norm launch failed");
+    const GemmPlan plan = gemm_plan(num_rows, s->vocab_pad, H, GEMM_STORE_F32, 1);
+    const hipError_t e = launch_gemm_bf16(s->h, H, s->w, H, logits, ld_logits, num_rows, s->vocab_pad, H, GEMM_STORE_F32,
+                                          plan.tile, 1, 0, st);
+    if (e != hipSuccess) return fail(s, GLLM_E_HIP, std::string("projection launch failed: ") + hipGetErrorString(e));
+    return GLLM_OK;
+}
+
+gllm_status gllm_op_sample(const float* logits, int64_t ld_logits, int32_t num_rows, int32_t vocab,
+                           const float* temperature, const int32_t* top_k, const float* top_p, const float* u,
+                           int32_t* out_ids, void* stream) {
+    if (!logits || !temperature || !top_k || !top_p || !u || !out_ids || num_rows < 0 || vocab < 1 || vocab > (1 << 24) ||
+        ld_logits < vocab)
+        return GLLM_E_INVALID;
+    if (num_rows == 0) return GLLM_OK;
+    sample_kernel<<<num_rows, kSampleThreads, 0, (hipStream_t)stream>>>(logits, ld_logits, vocab, temperature, top_k, top_p, u,
+                                                                        out_ids);
+    return hipGetLastError() == hipSuccess ? GLLM_OK : GLLM_E_HIP;
+}
+
+}  // extern "C"
