@@ -66,7 +66,15 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const bf16_t* __restrict_
 }
 
 // ---- sampling: one workgroup per row ----------------------------------------------------------------------
+// The row of logits (0.5 MB at a 128k vocabulary) does not fit on chip, so the cost is the number of passes over
+// it: 1 (maximum) + 4 (radix select of the k-th largest, only with top-k) + then either
+//   * at most kCompact tokens survive top-k (the usual top_k = 20..100): they are gathered into LDS once and
+//     nucleus and draw work on that short list, or
+//   * the nucleus threshold is searched over the whole row, 15 candidate thresholds per pass (8 passes), and the
+//     draw takes one more pass.
 constexpr int kSampleThreads = 1024;
+constexpr int kSampleWaves = kSampleThreads / 64;
+constexpr int kCompact = 1024;
 
 // order-preserving map from float to unsigned: a < b  <=>  key(a) < key(b) (for non-NaN values)
 __device__ __forceinline__ uint32_t float_key(float f) {
@@ -74,18 +82,26 @@ __device__ __forceinline__ uint32_t float_key(float f) {
     return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 
-// Sum over the workgroup, the same association for every call: thread-local values are combined by a fixed tree.
-__device__ __forceinline__ float block_sum(float v, float* scratch) {
+// Sum over the workgroup with a fixed association (lanes by butterfly, then the 16 wave sums in order), so that a
+// row always gives the same token.  `scratch` holds kSampleWaves floats per value.
+template <int N>
+__device__ __forceinline__ void block_sums(float (&v)[N], float* scratch) {
     const int tid = threadIdx.x;
-    scratch[tid] = v;
-    __syncthreads();
-    for (int s = kSampleThreads / 2; s > 0; s >>= 1) {
-        if (tid < s) scratch[tid] += scratch[tid + s];
-        __syncthreads();
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v[j] += __shfl_xor(v[j], o);
+        if ((tid & 63) == 0) scratch[j * kSampleWaves + (tid >> 6)] = v[j];
     }
-    const float r = scratch[0];
     __syncthreads();
-    return r;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSampleWaves; ++w) s += scratch[j * kSampleWaves + w];
+        v[j] = s;
+    }
+    __syncthreads();
 }
 
 __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __restrict__ logits, int64_t ld, int vocab,
@@ -94,15 +110,15 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
                                                                 const float* __restrict__ top_p,
                                                                 const float* __restrict__ uniform,
                                                                 int32_t* __restrict__ out) {
-    __shared__ float fs[kSampleThreads];
-    __shared__ int is[kSampleThreads];
+    __shared__ float fs[kSampleThreads];   // reductions; later the probabilities of the compact list
+    __shared__ int is[kSampleThreads];     // reductions; later the token ids of the compact list
     __shared__ unsigned hist[256];
     __shared__ uint32_t sh_key;
     __shared__ int sh_int;
     const int tid = threadIdx.x, row = blockIdx.x;
     const float* lg = logits + (int64_t)row * ld;
 
-    // the largest logit and its lowest index (greedy; also the softmax reference)
+    // pass 1: the largest logit and its lowest index (greedy; also the softmax reference)
     float best = -INFINITY;
     int best_i = INT_MAX;
     for (int i = tid; i < vocab; i += kSampleThreads) {
@@ -135,13 +151,17 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
         return;
     }
     const float zmax = best / temp;
+    const float p = top_p[row];
+    const float u = uniform[row];
 
-    // top-k: the k-th largest key by a radix select over the four bytes of the key, most significant first
-    uint32_t floor_key = 0;  // tokens with key >= floor_key are kept
+    // top-k: the k-th largest key by a radix select over the four bytes of the key, most significant first;
+    // tokens with key >= floor_key are kept (all of them when top-k is off)
+    uint32_t floor_key = 0;
+    int kept = vocab;
     const int k = top_k[row];
     if (k > 0 && k < vocab) {
         uint32_t prefix = 0;
-        int want = k;
+        int want = k, above_total = 0;
         for (int byte = 3; byte >= 0; --byte) {
             if (tid < 256) hist[tid] = 0;
             __syncthreads();
@@ -156,43 +176,145 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
                 int bin = 255, above = 0;
                 while (bin > 0 && above + (int)hist[bin] < want) above += (int)hist[bin--];
                 sh_key = prefix | ((uint32_t)bin << shift);
-                sh_int = want - above;
+                sh_int = above;
+                hist[0] = hist[bin];  // tokens that share the chosen byte (all equal to the k-th once byte 0 is done)
             }
             __syncthreads();
             prefix = sh_key;
-            want = sh_int;
+            want -= sh_int;
+            above_total += sh_int;
+            if (byte == 0) kept = above_total + (int)hist[0];
             __syncthreads();
         }
         floor_key = prefix;
     }
 
-    auto mass_from = [&](uint32_t from) {  // sum of exp(z - zmax) over the tokens with key >= from
-        float s = 0.f;
+    if (kept <= kCompact) {
+        // ---- short list: gather (probability, id), order by id, nucleus and draw on the list ----
+        if (tid == 0) sh_int = 0;
+        __syncthreads();
         for (int i = tid; i < vocab; i += kSampleThreads) {
             const float z = lg[i] / temp;
-            if (float_key(z) >= from) s += __expf(z - zmax);
+            if (float_key(z) >= floor_key) {
+                const int slot = atomicAdd(&sh_int, 1);
+                is[slot] = i;
+            }
         }
-        return block_sum(s, fs);
-    };
-    float total = mass_from(floor_key);
-
-    // nucleus: the largest key t with mass(key >= t) >= top_p * total, by bisection over the key space
-    const float p = top_p[row];
-    if (p < 1.f) {
-        const float need = p * total;
-        uint32_t lo = floor_key, hi = float_key(zmax);  // mass(>= lo) >= need holds; the answer is at most key(zmax)
-        // invariant: mass(>= lo) >= need, and mass(>= hi + 1) < need
-        while (lo < hi) {
-            const uint32_t mid = lo + (hi - lo + 1) / 2;
-            if (mass_from(mid) >= need) lo = mid;
-            else hi = mid - 1;
+        __syncthreads();
+        const int n = sh_int;
+        // bitonic sort of the ids (padding sorts last): the list is in index order whatever order the atomics took
+        if (tid >= n) is[tid] = INT_MAX;
+        __syncthreads();
+        for (int size = 2; size <= kCompact; size <<= 1)
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                const int partner = tid ^ stride;
+                if (partner > tid) {
+                    const int a = is[tid], b = is[partner];
+                    const bool up = (tid & size) == 0;
+                    if ((a > b) == up) {
+                        is[tid] = b;
+                        is[partner] = a;
+                    }
+                }
+                __syncthreads();
+            }
+        float z = 0.f, e = 0.f;
+        if (tid < n) {
+            z = lg[is[tid]] / temp;
+            e = __expf(z - zmax);
         }
-        floor_key = lo;
-        total = mass_from(floor_key);
+        const uint32_t my_key = tid < n ? float_key(z) : 0u;
+        float tot[1] = {e};
+        block_sums(tot, fs);
+        float total = tot[0];
+        if (p < 1.f) {
+            // the largest key t with mass(key >= t) >= p * total: bisection, the list stays in registers
+            const float need = p * total;
+            uint32_t lo = floor_key, hi = float_key(zmax);
+            while (lo < hi) {
+                const uint32_t mid = lo + (hi - lo + 1) / 2;
+                float m[1] = {(tid < n && my_key >= mid) ? e : 0.f};
+                block_sums(m, fs);
+                if (m[0] >= need) lo = mid;
+                else hi = mid - 1;
+            }
+            if (my_key < lo) e = 0.f;
+            float t2[1] = {e};
+            block_sums(t2, fs);
+            total = t2[0];
+        }
+        fs[tid] = e;
+        __syncthreads();
+        if (tid == 0) {  // the draw: first token in index order whose running sum exceeds u * total
+            const float target = u * total;
+            float running = 0.f;
+            int pick = -1, last = -1;
+            for (int j = 0; j < n; ++j) {
+                if (fs[j] > 0.f) {
+                    last = is[j];
+                    running += fs[j];
+                    if (running > target) {
+                        pick = last;
+                        break;
+                    }
+                }
+            }
+            out[row] = pick >= 0 ? pick : (last >= 0 ? last : best_i);
+        }
+        return;
     }
 
-    // draw in index order: every thread owns a run of consecutive tokens
-    const float target = uniform[row] * total;
+    // ---- long list: work on the whole row ----
+    auto masses = [&](const uint32_t (&from)[15], float (&m)[15]) {  // m[j] = sum of exp(z - zmax) over key >= from[j]
+#pragma unroll
+        for (int j = 0; j < 15; ++j) m[j] = 0.f;
+        for (int i = tid; i < vocab; i += kSampleThreads) {
+            const float z = lg[i] / temp;
+            const uint32_t key = float_key(z);
+            const float e = __expf(z - zmax);
+#pragma unroll
+            for (int j = 0; j < 15; ++j) m[j] += key >= from[j] ? e : 0.f;
+        }
+        block_sums(m, fs);
+    };
+    uint32_t probe[15];
+    float m[15];
+#pragma unroll
+    for (int j = 0; j < 15; ++j) probe[j] = floor_key;
+    masses(probe, m);
+    float total = m[0];
+    if (p < 1.f) {
+        // the largest key t with mass(key >= t) >= p * total; the interval [lo, hi] shrinks 16-fold per pass
+        const float need = p * total;
+        uint32_t lo = floor_key, hi = float_key(zmax);
+        while (lo < hi) {
+            const uint64_t span = (uint64_t)hi - lo;  // candidates lo < c_1 <= ... <= c_15 <= hi
+#pragma unroll
+            for (int j = 0; j < 15; ++j) probe[j] = lo + (uint32_t)((span * (j + 1) + 15) / 16);
+            masses(probe, m);
+            uint32_t new_lo = lo, new_hi = hi;
+            bool closed = false;
+#pragma unroll
+            for (int j = 0; j < 15; ++j) {
+                if (closed) continue;
+                if (m[j] >= need) new_lo = probe[j];
+                else {
+                    new_hi = probe[j] - 1;
+                    closed = true;
+                }
+            }
+            lo = new_lo;
+            hi = new_hi;
+        }
+        floor_key = lo;
+#pragma unroll
+        for (int j = 0; j < 15; ++j) probe[j] = floor_key;
+        masses(probe, m);
+        total = m[0];
+    }
+
+    // the draw in index order: every thread owns a run of consecutive tokens
+    const float target = u * total;
     const int run = (vocab + kSampleThreads - 1) / kSampleThreads;
     const int i0 = min(tid * run, vocab), i1 = min(i0 + run, vocab);
     float own = 0.f;
