@@ -14,6 +14,9 @@ Prints one JSON line:
                    mean end-to-end latency, tokens per second, preemptions -- for a pipeline of 4 equal stages whose
                    stage time follows a linear model fitted to this repository's measured stage kernels at the
                    70B-shaped configuration.  These are simulated figures, not serving measurements.
+  prefix_caching   the same trace with content: every prompt opens with one of a few shared system prompts.  Native
+                   simulation with the page pool's prefix cache (include/gllm_kv.h) on and off; a sample is checked
+                   against the oracle's simulation field by field.
 
 The trace stands in for the paper's ShareGPT-based workload (section 4.1): Poisson arrivals, log-normal prompt and
 output lengths; none of that data set's items is used.
@@ -23,6 +26,8 @@ import json
 import math
 import random
 import time
+
+import numpy as np
 
 from paper_2504_14775_amd import sched as S
 
@@ -40,6 +45,18 @@ def make_trace(n, rate_per_s, seed):
         prompt = int(min(4096, max(4, rng.lognormvariate(math.log(220), 0.9))))
         output = int(min(1024, max(1, rng.lognormvariate(math.log(180), 0.8))))
         out.append((int(t * 1e9), prompt, output))
+    return out
+
+
+def with_content(trace, groups, shared_tokens, seed):
+    """The same arrivals and lengths; each prompt starts with min(shared_tokens, its length - 1) tokens of one of
+    `groups` system prompts and goes on with tokens of its own."""
+    rng = random.Random(seed + 1)
+    stems = [[rng.randrange(32000) for _ in range(shared_tokens)] for _ in range(groups)]
+    out = []
+    for t, p, o in trace:
+        stem = rng.choice(stems)[:max(0, min(shared_tokens, p - 1))]
+        out.append((t, p, o, np.asarray(stem + [rng.randrange(32000, 64000) for _ in range(p - len(stem))], dtype=np.int32)))
     return out
 
 
@@ -67,6 +84,8 @@ def main():
     ap.add_argument("--rate", type=float, default=60.0, help="request arrivals per second in the simulated trace")
     ap.add_argument("--pages", type=int, default=60000, help="KV pool of the simulated deployment, pages of 16 tokens")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--prefix-groups", type=int, default=8, help="distinct system prompts in the trace with content")
+    ap.add_argument("--prefix-tokens", type=int, default=512, help="length of each system prompt")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     trace = make_trace(args.requests, args.rate, args.seed)
@@ -120,6 +139,32 @@ def main():
         }
     result["simulation"] = {"stage_time_model_ns": dict(zip(("base", "per_token", "per_decode_key", "per_1024_prefill_pairs"), MODEL)),
                             "arrival_rate_per_s": args.rate, "policies": sim}
+    # prefix caching: a trace whose prompts are longer by a shared system prompt
+    longer = [(t, p + args.prefix_tokens, o) for t, p, o in trace]
+    content = with_content(longer, args.prefix_groups, args.prefix_tokens, args.seed)
+    pc = {}
+    for name, on in (("cache_on", True), ("cache_off", False)):
+        prm = S.Params(policy=S.TOKEN_THROTTLING, prefix_caching=on, **base)
+        t0 = time.perf_counter()
+        r = S.gllm_sched_simulate(prm, MODEL, content)
+        wall = time.perf_counter() - t0
+        n = len(content)
+        pc[name] = {"prefix_hit_share_of_prompt_tokens": round(r["prefix_hit_tokens"] / sum(x[1] for x in content), 4),
+                    "tokens_computed": r["tokens"], "mean_ttft_ms": round(r["sum_ttft_ns"] / n / 1e6, 1),
+                    "mean_e2e_ms": round(r["sum_e2e_ns"] / n / 1e6, 1), "simulated_seconds": round(r["end_ns"] / 1e9, 2),
+                    "micro_batches": r["batches"], "preemptions": r["preemptions"],
+                    "micro_batches_per_wall_s": round(r["batches"] / wall, 1)}
+    if not args.no_cpu_baseline:
+        from oracle import throttle_oracle as T
+        sample = [(t, p, o, tk.tolist()) for t, p, o, tk in content[:max(50, args.requests // 10)]]
+        prm = dict(policy=T.THROTTLE, prefix_caching=True, **base)
+        t0 = time.perf_counter()
+        ro = T.simulate(T.Params(**prm), T.StageModel(*MODEL), sample)
+        osecs = time.perf_counter() - t0
+        assert S.gllm_sched_simulate(S.Params(**prm), MODEL, sample) == ro, "native and oracle simulations disagree (prefix caching)"
+        pc["oracle_sample"] = {"micro_batches_per_s": round(ro["batches"] / osecs, 1), "requests": len(sample), "equal": True}
+    result["prefix_caching"] = {"workload": f"{args.prefix_groups} system prompts of {args.prefix_tokens} tokens in front of the same trace",
+                                **pc}
     print(json.dumps(result))
 
 

@@ -33,17 +33,17 @@ typedef struct gllm_sched_params {
     int32_t token_budget;  /* chunked-prefill baseline: new tokens per micro-batch */
     int32_t use_wt;        /* 0 drops the waiting-tokens term of Eq. 3 (the paper's "w/o WT" ablation) */
     int32_t use_ut;        /* 0 drops the idle-rate term of Eq. 3 ("w/o UT"); the threshold still suspends prefill */
-    int32_t reserved;
+    int32_t prefix_caching; /* 1: requests added with their token ids share cached whole pages of equal prompt prefixes */
     int64_t total_pages;   /* size of the KV pool the scheduler hands out */
 } gllm_sched_params;
 
-/* Eq. 3 (section 3.2, with Eq. 1, Eq. 2 and the threshold as special cases): prefill tokens to batch now, given
+/* Eq. 3 (section 3.1, with Eq. 1, Eq. 2 and the threshold as special cases): prefill tokens to batch now, given
  * the prompt tokens awaiting prefill (#WP) and the free pages (idle rate KV_free = free_pages / total_pages).
  * Integer arithmetic: #WP / #T rounds up, #MaxP x (KV_free - KV_thresh) / (1 - KV_thresh) rounds down; an idle
  * rate below the threshold gives 0; the result never exceeds wp or max_p.  Returns -1 for invalid arguments. */
 int64_t gllm_sched_prefill_budget(const gllm_sched_params* p, int64_t wp, int64_t free_pages);
 
-/* Eq. 4 (section 3.3): decode rows per micro-batch = ceil(#RD / #PP_depth).  Returns -1 for invalid arguments. */
+/* Eq. 4 (section 3.2): decode rows per micro-batch = ceil(#RD / #PP_depth).  Returns -1 for invalid arguments. */
 int64_t gllm_sched_decode_budget(const gllm_sched_params* p, int64_t rd);
 
 gllm_status gllm_sched_create(const gllm_sched_params* p, gllm_sched** out);
@@ -53,11 +53,22 @@ void gllm_sched_destroy(gllm_sched* s);
  * ends when it has produced output_len tokens (the last prefill chunk produces the first). */
 gllm_status gllm_sched_add_request(gllm_sched* s, int64_t request_id, int32_t prompt_len, int32_t output_len);
 
-/* Forms the next micro-batch (section 3.1: decode and prefill tokens are budgeted separately, then merged).
+/* The same with the prompt's token ids (prompt_tokens[0 .. prompt_len), copied).  With prefix_caching = 1 the
+ * scheduler's page pool is the one of gllm_kv.h (section 3.4 lists prefix caching among the integrated techniques):
+ * a request about to receive its first chunk -- or starting over after a preemption -- looks its prompt up and
+ * skips the whole pages found (cached_len of its first chunk is then 16 x pages found; at least one token is always
+ * left to compute); whole pages of this prompt are registered when the chunk that fills them has left the last
+ * stage, until one registration fails; registered pages nobody holds count as free pages in Eq. 3.  Generated tokens
+ * are never registered.  Shared pages are only read: a chunk's new tokens always start on a page of its own.  With
+ * prefix_caching = 0, or a null prompt_tokens, this is gllm_sched_add_request(). */
+gllm_status gllm_sched_add_request_tokens(gllm_sched* s, int64_t request_id, const int32_t* prompt_tokens, int32_t prompt_len,
+                                          int32_t output_len);
+
+/* Forms the next micro-batch (opening of section 3: decode and prefill tokens are budgeted separately, then merged).
  * Outputs (each with room for `capacity` rows): request ids, new-token counts, cached lengths; decode rows (one
  * new token) come first, then prefill chunks in queue order.  *num_rows = 0 and *batch_id = -1 when the pipeline
  * already holds pp_depth micro-batches or nothing can be scheduled.  Pages for the new tokens are assigned here,
- * before the micro-batch runs (caption of the prefill case study, section 3.2).  A request is in at most one
+ * before the micro-batch runs (caption of the prefill case study, section 3.1).  A request is in at most one
  * micro-batch in flight.  GLLM_E_CAPACITY (and no change) when capacity is below the number of requests that
  * are waiting or idle in their decode phase (each contributes at most one row). */
 gllm_status gllm_sched_next_batch(gllm_sched* s, int64_t* batch_id, int64_t* request_ids, int32_t* new_tokens,
@@ -75,10 +86,13 @@ gllm_status gllm_sched_complete_batch(gllm_sched* s, int64_t batch_id, int64_t* 
 typedef struct gllm_sched_state {
     int64_t tokens_waiting;   /* #WP */
     int64_t decode_requests;  /* #RD */
-    int64_t free_pages;
+    int64_t free_pages;       /* pages that can be handed out: never used, returned, or cached without a holder */
     int64_t batches_in_flight;
     int64_t waiting_requests;
-    int64_t preemptions;      /* decode requests sent back to the waiting queue for recomputation so far */
+    int64_t preemptions;      /* requests sent back for recomputation so far */
+    int64_t idle_cached_pages; /* the part of free_pages that still holds a registered prefix */
+    int64_t prefix_hit_tokens; /* prompt tokens skipped thanks to cached pages so far */
+    int64_t evictions;        /* cached pages recycled so far */
 } gllm_sched_state;
 gllm_status gllm_sched_get_state(const gllm_sched* s, gllm_sched_state* out);
 
@@ -93,12 +107,18 @@ typedef struct gllm_stage_time_model {
 
 typedef struct gllm_sim_result {
     int64_t end_ns, batches, tokens, busy_ns_last_stage, bubble_ppm_last_stage, mean_batch_tokens_x1000,
-        var_batch_tokens_x1000, sum_ttft_ns, sum_e2e_ns, preemptions;
+        var_batch_tokens_x1000, sum_ttft_ns, sum_e2e_ns, preemptions, prefix_hit_tokens;
 } gllm_sim_result;
 
 gllm_status gllm_sched_simulate(const gllm_sched_params* p, const gllm_stage_time_model* model,
                                 const int64_t* arrival_ns, const int32_t* prompt_len, const int32_t* output_len,
                                 int64_t num_requests, gllm_sim_result* out);
+
+/* The same with token ids: prompt_tokens holds the prompts back to back in arrival order (sum of prompt_len
+ * entries); null = no content.  Only matters with prefix_caching = 1. */
+gllm_status gllm_sched_simulate_tokens(const gllm_sched_params* p, const gllm_stage_time_model* model,
+                                       const int64_t* arrival_ns, const int32_t* prompt_len, const int32_t* output_len,
+                                       const int32_t* prompt_tokens, int64_t num_requests, gllm_sim_result* out);
 
 #ifdef __cplusplus
 }

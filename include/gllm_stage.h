@@ -5,13 +5,13 @@
  * chunked-prefill and decode tokens, the computation that a pipeline-parallel serving
  * runtime with Token Throttling (arxiv 2504.14775) schedules:
  *   - a stage worker receives activations, runs its share of decoder layers, and hands
- *     activations on (paper section 3.4, description of the workers);
- *   - prefill and decode tokens are merged into a single batch (section 3.1); a prompt may
+ *     activations on (paper section 3.3, description of the workers);
+ *   - prefill and decode tokens are merged into a single batch (opening of section 3); a prompt may
  *     be prefilled in chunks that attend to the chunks already cached (section 2.2,
  *     "Scheduling Policies");
  *   - the KV cache is paged and every stage shares one set of page tables; pages for the
- *     new tokens are assigned before the micro-batch runs (section 3.4; caption of the
- *     prefill case-study figure in section 3.2), so this library never allocates KV pages:
+ *     new tokens are assigned before the micro-batch runs (section 3.3; caption of the
+ *     prefill case-study figure in section 3.1), so this library never allocates KV pages:
  *     it only writes K/V into the pages the caller's tables name;
  *   - weights and activations are bf16 (section 4.1).
  * The layer arithmetic is the public Llama/Qwen decoder layer: pre-norm RMSNorm, QKV

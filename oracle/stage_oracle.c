@@ -11,7 +11,7 @@
  *   - section 2.2: prefill processes a prompt's tokens in parallel and fills the KV cache; a
  *     decode step attends the newest token to the stored KV cache; a long prompt may be
  *     computed in chunks over several iterations, mixed with decode tokens in one batch;
- *   - section 3.1 / 3.4: prefill and decode tokens are merged into a single batch; the KV cache
+ *   - section 3 (opening) / 3.3: prefill and decode tokens are merged into a single batch; the KV cache
  *     is paged, with page tables shared by every stage, pages being assigned before the
  *     micro-batch runs;
  *   - section 4.1: bf16 weights and activations.

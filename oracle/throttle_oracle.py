@@ -4,14 +4,14 @@ Only tests/ (and the bench scripts' baseline legs) may import this module; the l
 
 What is stated here, with the passage of arxiv 2504.14775 each part follows:
 
-* prefill_budget():  Prefill Token Throttling, section 3.2: Eq. 1 (throttling by tokens awaiting prefill, WT),
+* prefill_budget():  Prefill Token Throttling, section 3.1: Eq. 1 (throttling by tokens awaiting prefill, WT),
   Eq. 2 (throttling by KV-cache idle rate, UT), the idle-rate threshold, and their combination Eq. 3.
-* decode_budget():   Decode Token Throttling, section 3.3, Eq. 4.
+* decode_budget():   Decode Token Throttling, section 3.2, Eq. 4.
 * Scheduler:         the iteration-level scheduler that turns the two budgets into one merged micro-batch
-  (section 3.1: prefill and decode tokens are scheduled separately, then merged), with the chunked-prefill
+  (opening of section 3: prefill and decode tokens are scheduled separately, then merged), with the chunked-prefill
   baseline of section 2.2 (all decode requests first, then prefill chunks up to a fixed token budget) as the
   other policy.  KV pages are assigned before a micro-batch runs and released when a request ends (caption of
-  the prefill case study, section 3.2); at most pipeline-depth micro-batches are in flight (section 3.3).
+  the prefill case study, section 3.1); at most pipeline-depth micro-batches are in flight (section 3.2).
 * simulate():        a pipeline of `pp_depth` equal stages fed by that scheduler, with a linear stage-time model.
   Not from the paper: a measuring device for bubbles and token-count variance.
 
@@ -26,19 +26,27 @@ Readings where the paper is silent or at odds with itself (each is a parameter-f
       in flight or not; decode requests are taken in least-recently-run order.
   R6  a decode request that needs a page when none is free preempts the most recently admitted idle decode
       request (pages released, the request re-enters the waiting queue at its front with its generated tokens
-      appended to its prompt: recomputation, section 3.2 "Threshold"); with no such victim it takes the pages
+      appended to its prompt: recomputation, section 3.1 "Threshold"); with no such victim it takes the pages
       of the last waiting request that holds some and is not in flight (that request starts over); with no
       victim at all it waits.  The first schedulable waiting request, when no page is left for it, likewise
       takes the pages of waiting requests behind it, last first.  Without these two rules a small pool can
       fill up with half-prefilled prompts and stop for good.
   R7  all arithmetic is integer; the threshold is given in 1/10000.
-  R8  pages come from a last-in-first-out free list that first hands out 0, 1, 2, ...; a request's pages return
-      to it in block-table order.  (Placement policy is not the paper's subject; fixed here so that two
-      implementations can be compared id by id.)
+  R8  pages come from the page pool of kv_oracle.py: a last-in-first-out free stack that first hands out 0, 1,
+      2, ...; a request's pages return to it in block-table order.  (Placement policy is not the paper's
+      subject; fixed here so that two implementations can be compared id by id.)
+  R9  with prefix caching (section 3.4 lists it among the integrated techniques; off in the paper's runs,
+      section 4.1) a request that is about to receive its first chunk, or starts over after a preemption, first
+      looks its prompt up in the pool and skips the whole pages found, leaving at least one token to compute;
+      whole pages of the prompt as given on arrival are registered when the chunk that fills them has left the
+      last stage, until one registration fails; pages nobody holds that still carry a registered prefix count
+      as idle KV memory in Eq. 2 / Eq. 3 (they are reclaimed on demand).  Generated tokens are never registered.
 """
 from collections import deque
 from dataclasses import dataclass
-from typing import Dict, List, Optional, Tuple
+from typing import Dict, List, Optional, Sequence, Tuple
+
+from .kv_oracle import ROOT, PagePool
 
 PAGE = 16
 SARATHI, THROTTLE = 0, 1
@@ -57,6 +65,7 @@ class Params:
     use_wt: bool = True
     use_ut: bool = True
     total_pages: int = 4096
+    prefix_caching: bool = False
 
 
 def ceil_div(a: int, b: int) -> int:
@@ -95,6 +104,9 @@ class Request:
     chunk: int = 0          # tokens of the chunk in flight
     admitted: int = -1      # order of entering the decode phase (for R6)
     block_table: list = None
+    tokens: Optional[list] = None   # the prompt as given on arrival (R9)
+    registered: int = 0             # leading pages of the block table that are in the pool's tree
+    registering: bool = True
 
 
 class Scheduler:
@@ -104,31 +116,55 @@ class Scheduler:
         self.waiting: deque = deque()        # request ids with prompt tokens left, FIFO
         self.ready: deque = deque()          # decode requests not in flight, least recently run first
         self.n_decode = 0                    # requests in the decode phase (#RD)
-        self.free_list = list(range(params.total_pages - 1, -1, -1))   # R8
+        self.pool = PagePool(params.total_pages)                              # R8
         self.in_flight: Dict[int, List[Tuple[int, int, int, bool]]] = {}
         self.next_bid = 0
         self.admit_counter = 0
         self.finished: List[int] = []
         self.preemptions = 0
+        self.hit_tokens = 0                  # prompt tokens skipped thanks to the prefix cache
 
     @property
     def free_pages(self) -> int:
-        return len(self.free_list)
+        return self.pool.available()
 
     def _take(self, r: Request, need: int) -> None:
         for _ in range(need):
-            r.block_table.append(self.free_list.pop())
+            r.block_table.append(self.pool.alloc())
         r.pages += need
 
     def _release(self, r: Request) -> None:
-        self.free_list.extend(r.block_table)
+        self.pool.release(r.block_table)
         r.block_table = []
         r.pages = 0
+        r.registered = 0
+        r.registering = True
+
+    def _lookup(self, r: Request) -> None:
+        """R9: the cached whole pages of the prompt become the start of the block table."""
+        found = self.pool.match(r.tokens, (r.prompt_len - 1) // PAGE)
+        r.block_table = list(found)
+        r.pages = r.registered = len(found)
+        r.prefilled = len(found) * PAGE
+        self.hit_tokens += r.prefilled
+
+    def _register(self, r: Request) -> None:
+        """R9: the pages a completed chunk has filled with tokens of the original prompt enter the tree."""
+        full = min(r.prefilled, len(r.tokens)) // PAGE
+        while r.registering and r.registered < full:
+            i = r.registered
+            parent = r.block_table[i - 1] if i > 0 else ROOT
+            if self.pool.register(parent, r.tokens[i * PAGE:(i + 1) * PAGE], r.block_table[i]):
+                r.registered += 1
+            else:
+                r.registering = False
 
     # ---- state -------------------------------------------------------------------------------------------
-    def add_request(self, rid: int, prompt_len: int, output_len: int) -> None:
+    def add_request(self, rid: int, prompt_len: int, output_len: int, tokens: Optional[Sequence[int]] = None) -> None:
         assert rid not in self.req and prompt_len >= 1 and output_len >= 1
-        self.req[rid] = Request(rid, prompt_len, output_len, block_table=[])
+        assert tokens is None or len(tokens) == prompt_len
+        keep = list(tokens) if tokens is not None and self.p.prefix_caching else None
+        self.req[rid] = Request(rid, prompt_len, output_len, block_table=[], tokens=keep)
         self.waiting.append(rid)
 
     def tokens_waiting(self) -> int:
@@ -180,6 +216,8 @@ class Scheduler:
             r = self.req[rid]
             if r.in_flight:
                 continue
+            if r.tokens is not None and r.prefilled == 0 and r.pages == 0:
+                self._lookup(r)
             c = r.prefilled
             n = min(r.prompt_len - c, budget)
             fit = (r.pages + self.free_pages) * PAGE - c                      # R3: what the free pages can hold
@@ -239,6 +277,8 @@ class Scheduler:
             else:
                 r.chunk = 0
                 r.prefilled += n
+                if r.tokens is not None:
+                    self._register(r)
                 if r.prefilled < r.prompt_len:
                     continue
                 self.waiting.remove(rid)
@@ -279,7 +319,7 @@ class StageModel:
 
 
 def simulate(params: Params, model: StageModel, arrivals: List[Tuple[int, int, int]]):
-    """arrivals: [(arrival time ns, prompt_len, output_len)] sorted by time; request ids are their indices.
+    """arrivals: [(arrival time ns, prompt_len, output_len[, prompt tokens])] sorted by time; ids are their indices.
     Stage s of micro-batch j starts when stage s-1 of j and stage s of j-1 are both done.  The scheduler runs
     whenever stage 0 is free, fewer than pp_depth micro-batches are in flight and something can be scheduled.
     Returns a dict of integers (times in ns)."""
@@ -296,7 +336,7 @@ def simulate(params: Params, model: StageModel, arrivals: List[Tuple[int, int, i
     n = len(arrivals)
     while len(finish) < n:
         while nxt < n and arrivals[nxt][0] <= now:
-            sched.add_request(nxt, arrivals[nxt][1], arrivals[nxt][2])
+            sched.add_request(nxt, *arrivals[nxt][1:])
             nxt += 1
         while completions and completions[0][0] <= now:
             t, bid = completions.pop(0)
@@ -352,4 +392,5 @@ def simulate(params: Params, model: StageModel, arrivals: List[Tuple[int, int, i
         "sum_ttft_ns": sum(first_token[i] - arrivals[i][0] for i in range(n)),
         "sum_e2e_ns": sum(finish[i] - arrivals[i][0] for i in range(n)),
         "preemptions": sched.preemptions,
+        "prefix_hit_tokens": sched.hit_tokens,
     }

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgllm_stage.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 SOURCES = ["gllm_stage.hip", "kernels_gemm.hip", "kernels_attn.hip", "kernels_misc.hip", "kernels_peak.hip",
-           "gllm_head.hip", "gllm_sched.cpp"]   # the last one is host code only (the micro-batch scheduler)
+           "gllm_head.hip", "gllm_sched.cpp", "gllm_kv.cpp"]   # the last two are host code only (scheduler, KV page pool)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -10,6 +10,8 @@
 #include <unordered_map>
 #include <vector>
 
+#include "page_pool.h"
+
 namespace {
 
 constexpr int64_t kPageTokens = 16;
@@ -20,7 +22,8 @@ inline int64_t div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
 bool params_ok(const gllm_sched_params* p) {
     return p && (p->policy == GLLM_POLICY_CHUNKED_PREFILL || p->policy == GLLM_POLICY_TOKEN_THROTTLING) &&
            p->iters_t >= 1 && p->min_p >= 1 && p->max_p >= p->min_p && p->kv_thresh_bp >= 0 && p->kv_thresh_bp <= 9999 &&
-           p->pp_depth >= 1 && p->token_budget >= 1 && p->total_pages >= 1 && p->total_pages <= (int64_t)1 << 31;
+           p->pp_depth >= 1 && p->token_budget >= 1 && p->total_pages >= 1 && p->total_pages < (int64_t)1 << 31 &&
+           (p->prefix_caching == 0 || p->prefix_caching == 1);
 }
 
 // Eq. 3.  The idle-rate comparison and the idle-rate term are kept in integers: KV_free = free / total and
@@ -44,6 +47,11 @@ struct Seq {
     int64_t decode_rank = -1;  // order of entering the decode phase
     bool flying = false;
     std::vector<int32_t> pages;
+    // prefix caching: the prompt as given on arrival, how many leading pages of `pages` are in the pool's tree,
+    // and whether this request still registers the pages it fills
+    std::vector<int32_t> tokens;
+    int64_t entered = 0;
+    bool entering = true;
 };
 
 struct Row {
@@ -59,23 +67,49 @@ struct gllm_sched {
     std::unordered_map<int64_t, Seq> seqs;
     std::deque<int64_t> waiting;  // first come, first served
     std::deque<int64_t> idle_decode;  // decode requests not in flight, least recently run in front
-    std::vector<int32_t> free_pages;  // stack; the top is handed out next
+    gllm::PagePool pool;
     std::unordered_map<int64_t, std::vector<Row>> flying;
-    int64_t decode_total = 0, waiting_tokens = 0, next_batch_id = 0, next_rank = 0, preempted = 0;
+    int64_t decode_total = 0, waiting_tokens = 0, next_batch_id = 0, next_rank = 0, preempted = 0, hit_tokens = 0;
 
-    explicit gllm_sched(const gllm_sched_params& q) : p(q) {
-        free_pages.resize((size_t)q.total_pages);
-        for (int64_t i = 0; i < q.total_pages; ++i) free_pages[(size_t)i] = (int32_t)(q.total_pages - 1 - i);
+    explicit gllm_sched(const gllm_sched_params& q) : p(q), pool(q.total_pages) {}
+    void admit(int64_t id, int32_t prompt_len, int32_t output_len, const int32_t* tokens) {
+        Seq q;
+        q.prompt = prompt_len;
+        q.output = output_len;
+        if (tokens && p.prefix_caching) q.tokens.assign(tokens, tokens + prompt_len);
+        seqs.emplace(id, std::move(q));
+        waiting.push_back(id);
+        waiting_tokens += prompt_len;
     }
+    int64_t spare() const { return pool.available(); }
     void grab(Seq& s, int64_t n) {
-        for (int64_t i = 0; i < n; ++i) {
-            s.pages.push_back(free_pages.back());
-            free_pages.pop_back();
-        }
+        for (int64_t i = 0; i < n; ++i) s.pages.push_back(pool.alloc());
     }
     void give_back(Seq& s) {
-        free_pages.insert(free_pages.end(), s.pages.begin(), s.pages.end());
+        pool.release(s.pages.data(), s.pages.size());
         s.pages.clear();
+        s.entered = 0;
+        s.entering = true;
+    }
+    // A request about to receive its first chunk (again): the cached whole pages of its prompt open its block
+    // table, but at least one token is left to compute.
+    void look_up(Seq& s) {
+        const int64_t found = pool.match(s.tokens.data(), (int64_t)s.tokens.size(), (s.prompt - 1) / kPageTokens, s.pages);
+        s.entered = found;
+        s.prefilled = found * kPageTokens;
+        waiting_tokens -= s.prefilled;
+        hit_tokens += s.prefilled;
+    }
+    // The whole pages a finished chunk has filled with tokens of the original prompt enter the pool's tree, until a
+    // page turns out to be there already.
+    void enter_filled_pages(Seq& s) {
+        const int64_t whole = std::min<int64_t>(s.prefilled, (int64_t)s.tokens.size()) / kPageTokens;
+        while (s.entering && s.entered < whole) {
+            const size_t i = (size_t)s.entered;
+            const int32_t parent = i ? s.pages[i - 1] : gllm::PagePool::kRoot;
+            if (pool.enter(parent, s.tokens.data() + i * kPageTokens, s.pages[i])) ++s.entered;
+            else s.entering = false;
+        }
     }
     // Recomputation: the request goes back to the head of the waiting queue, its output so far becomes prompt.
     void evict(int64_t id) {
@@ -110,14 +144,14 @@ struct gllm_sched {
     std::vector<Row> plan() {
         std::vector<Row> rows;
         if ((int64_t)flying.size() >= p.pp_depth) return rows;
-        const int64_t free_before = (int64_t)free_pages.size();
+        const int64_t free_before = spare();
         int64_t slots = p.policy == GLLM_POLICY_TOKEN_THROTTLING ? div_up(decode_total, p.pp_depth) : p.token_budget;
         for (; slots > 0 && !idle_decode.empty(); --slots) {
             const int64_t id = idle_decode.front();
             Seq& s = seqs[id];
             const int64_t cached = s.prompt + s.produced - 1;
             const int64_t extra = div_up(cached + 1, kPageTokens) - (int64_t)s.pages.size();
-            while (extra > (int64_t)free_pages.size()) {
+            while (extra > spare()) {
                 int64_t victim = -1, best = -1;
                 for (int64_t other : idle_decode)
                     if (other != id && seqs[other].decode_rank > best) {
@@ -127,7 +161,7 @@ struct gllm_sched {
                 if (victim >= 0) evict(victim);
                 else if (!strip_last_waiting(0)) break;
             }
-            if (extra > (int64_t)free_pages.size()) break;
+            if (extra > spare()) break;
             idle_decode.pop_front();
             grab(s, extra);
             s.flying = true;
@@ -140,7 +174,8 @@ struct gllm_sched {
         for (size_t i = 0; i < waiting.size() && left > 0; ++i) {
             Seq& s = seqs[waiting[i]];
             if (s.flying) continue;
-            auto room_for = [&]() { return ((int64_t)s.pages.size() + (int64_t)free_pages.size()) * kPageTokens - s.prefilled; };
+            if (!s.tokens.empty() && s.prefilled == 0 && s.pages.empty()) look_up(s);
+            auto room_for = [&]() { return ((int64_t)s.pages.size() + spare()) * kPageTokens - s.prefilled; };
             int64_t room = room_for();
             while (room <= 0 && strip_last_waiting(i + 1)) room = room_for();
             if (room <= 0) break;  // the head of the queue blocks the rest
@@ -173,6 +208,7 @@ struct gllm_sched {
             } else {
                 s.chunk = 0;
                 s.prefilled += r.count;
+                if (!s.tokens.empty()) enter_filled_pages(s);
                 if (s.prefilled < s.prompt) continue;
                 waiting.erase(std::find(waiting.begin(), waiting.end(), r.id));
                 s.produced = 1;
@@ -215,17 +251,17 @@ gllm_status gllm_sched_create(const gllm_sched_params* p, gllm_sched** out) {
 
 void gllm_sched_destroy(gllm_sched* s) { delete s; }
 
-gllm_status gllm_sched_add_request(gllm_sched* s, int64_t request_id, int32_t prompt_len, int32_t output_len) {
+gllm_status gllm_sched_add_request_tokens(gllm_sched* s, int64_t request_id, const int32_t* prompt_tokens, int32_t prompt_len,
+                                          int32_t output_len) {
     if (!s || prompt_len < 1 || output_len < 1 || s->seqs.count(request_id)) return GLLM_E_INVALID;
     // a request that could never fit in the pool, even alone, is refused instead of blocking the queue for ever
     if (div_up((int64_t)prompt_len + output_len, kPageTokens) > s->p.total_pages) return GLLM_E_CAPACITY;
-    Seq q;
-    q.prompt = prompt_len;
-    q.output = output_len;
-    s->seqs.emplace(request_id, std::move(q));
-    s->waiting.push_back(request_id);
-    s->waiting_tokens += prompt_len;
+    s->admit(request_id, prompt_len, output_len, prompt_tokens);
     return GLLM_OK;
+}
+
+gllm_status gllm_sched_add_request(gllm_sched* s, int64_t request_id, int32_t prompt_len, int32_t output_len) {
+    return gllm_sched_add_request_tokens(s, request_id, nullptr, prompt_len, output_len);
 }
 
 gllm_status gllm_sched_next_batch(gllm_sched* s, int64_t* batch_id, int64_t* request_ids, int32_t* new_tokens,
@@ -279,16 +315,25 @@ gllm_status gllm_sched_get_state(const gllm_sched* s, gllm_sched_state* out) {
     if (!s || !out) return GLLM_E_INVALID;
     out->tokens_waiting = s->waiting_tokens;
     out->decode_requests = s->decode_total;
-    out->free_pages = (int64_t)s->free_pages.size();
+    out->free_pages = s->spare();
     out->batches_in_flight = (int64_t)s->flying.size();
     out->waiting_requests = (int64_t)s->waiting.size();
     out->preemptions = s->preempted;
+    out->idle_cached_pages = s->pool.idle_cached();
+    out->prefix_hit_tokens = s->hit_tokens;
+    out->evictions = s->pool.evictions();
     return GLLM_OK;
 }
 
 gllm_status gllm_sched_simulate(const gllm_sched_params* p, const gllm_stage_time_model* model,
                                 const int64_t* arrival_ns, const int32_t* prompt_len, const int32_t* output_len,
                                 int64_t num_requests, gllm_sim_result* out) {
+    return gllm_sched_simulate_tokens(p, model, arrival_ns, prompt_len, output_len, nullptr, num_requests, out);
+}
+
+gllm_status gllm_sched_simulate_tokens(const gllm_sched_params* p, const gllm_stage_time_model* model,
+                                       const int64_t* arrival_ns, const int32_t* prompt_len, const int32_t* output_len,
+                                       const int32_t* prompt_tokens, int64_t num_requests, gllm_sim_result* out) {
     if (!params_ok(p) || !model || !arrival_ns || !prompt_len || !output_len || !out || num_requests < 1)
         return GLLM_E_INVALID;
     for (int64_t i = 0; i < num_requests; ++i) {
@@ -298,18 +343,15 @@ gllm_status gllm_sched_simulate(const gllm_sched_params* p, const gllm_stage_tim
     }
     gllm_sched sch(*p);
     const int depth = p->pp_depth;
+    int64_t token_cursor = 0;  // start of the next arriving prompt in prompt_tokens
     std::vector<int64_t> stage_free((size_t)depth, 0), first_token((size_t)num_requests, -1), ended_at((size_t)num_requests, -1);
     std::vector<std::pair<int64_t, int64_t>> landing;  // (time the micro-batch leaves the last stage, batch id), ascending
     int64_t busy_last = 0, clock = 0, arrived = 0, ended = 0, batches = 0, token_sum = 0;
     std::vector<int64_t> batch_tokens;
     while (true) {
         for (; arrived < num_requests && arrival_ns[arrived] <= clock; ++arrived) {
-            Seq q;
-            q.prompt = prompt_len[arrived];
-            q.output = output_len[arrived];
-            sch.seqs.emplace(arrived, std::move(q));
-            sch.waiting.push_back(arrived);
-            sch.waiting_tokens += prompt_len[arrived];
+            sch.admit(arrived, prompt_len[arrived], output_len[arrived], prompt_tokens ? prompt_tokens + token_cursor : nullptr);
+            token_cursor += prompt_len[arrived];
         }
         while (!landing.empty() && landing.front().first <= clock) {
             const int64_t t = landing.front().first, b = landing.front().second;
@@ -380,6 +422,7 @@ gllm_status gllm_sched_simulate(const gllm_sched_params* p, const gllm_stage_tim
     out->sum_ttft_ns = ttft;
     out->sum_e2e_ns = e2e;
     out->preemptions = sch.preempted;
+    out->prefix_hit_tokens = sch.hit_tokens;
     return GLLM_OK;
 }
 

@@ -1,7 +1,7 @@
 // C ABI and host-side executor of the stage forward (see include/gllm_stage.h).
 //
 // A forward call validates the batch descriptor, builds the per-batch metadata once (it is
-// shared by all layers because every layer uses the same page tables, paper section 3.4),
+// shared by all layers because every layer uses the same page tables, paper section 3.3),
 // uploads it with one asynchronous copy from pinned staging, and enqueues, per layer:
 //   RMSNorm -> QKV GEMM -> RoPE + paged KV write -> prefill attention, decode attention (+merge)
 //   -> O GEMM -> residual add + RMSNorm -> gate/up GEMM (SwiGLU) -> down GEMM -> (residual add fused into the
@@ -9,7 +9,7 @@
 // and finally the last residual add with the cast of the fp32 residual stream to bf16.  The O and down
 // projections may be split along k; their partial products are summed in fixed order by the consumer.  Nothing in the call waits for the
 // device, so consecutive batches queue back to back (the host-side preparation of batch i+1
-// overlaps the execution of batch i, the "metadata ahead of data" idea of section 3.4).
+// overlaps the execution of batch i, the "metadata ahead of data" idea of section 3.3).
 #include "../../include/gllm_stage.h"
 #include "common.h"
 

@@ -11,8 +11,8 @@ from .binding import GLLM_OK, GllmError, load_library
 
 EXPORTS = [
     "gllm_sched_prefill_budget", "gllm_sched_decode_budget", "gllm_sched_create", "gllm_sched_destroy",
-    "gllm_sched_add_request", "gllm_sched_next_batch", "gllm_sched_batch_block_tables",
-    "gllm_sched_complete_batch", "gllm_sched_get_state", "gllm_sched_simulate",
+    "gllm_sched_add_request", "gllm_sched_add_request_tokens", "gllm_sched_next_batch", "gllm_sched_batch_block_tables",
+    "gllm_sched_complete_batch", "gllm_sched_get_state", "gllm_sched_simulate", "gllm_sched_simulate_tokens",
 ]
 
 CHUNKED_PREFILL, TOKEN_THROTTLING = 0, 1
@@ -21,12 +21,13 @@ CHUNKED_PREFILL, TOKEN_THROTTLING = 0, 1
 class gllm_sched_params(C.Structure):
     _fields_ = [("policy", C.c_int32), ("iters_t", C.c_int32), ("max_p", C.c_int32), ("min_p", C.c_int32),
                 ("kv_thresh_bp", C.c_int32), ("pp_depth", C.c_int32), ("token_budget", C.c_int32),
-                ("use_wt", C.c_int32), ("use_ut", C.c_int32), ("reserved", C.c_int32), ("total_pages", C.c_int64)]
+                ("use_wt", C.c_int32), ("use_ut", C.c_int32), ("prefix_caching", C.c_int32), ("total_pages", C.c_int64)]
 
 
 class gllm_sched_state(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("tokens_waiting", "decode_requests", "free_pages", "batches_in_flight",
-                                         "waiting_requests", "preemptions")]
+                                         "waiting_requests", "preemptions", "idle_cached_pages", "prefix_hit_tokens",
+                                         "evictions")]
 
 
 class gllm_stage_time_model(C.Structure):
@@ -34,7 +35,7 @@ class gllm_stage_time_model(C.Structure):
 
 
 SIM_FIELDS = ("end_ns", "batches", "tokens", "busy_ns_last_stage", "bubble_ppm_last_stage", "mean_batch_tokens_x1000",
-              "var_batch_tokens_x1000", "sum_ttft_ns", "sum_e2e_ns", "preemptions")
+              "var_batch_tokens_x1000", "sum_ttft_ns", "sum_e2e_ns", "preemptions", "prefix_hit_tokens")
 
 
 class gllm_sim_result(C.Structure):
@@ -53,10 +54,11 @@ class Params:
     use_wt: bool = True
     use_ut: bool = True
     total_pages: int = 4096
+    prefix_caching: bool = False
 
     def c(self) -> gllm_sched_params:
         return gllm_sched_params(self.policy, self.iters_t, self.max_p, self.min_p, self.kv_thresh_bp, self.pp_depth,
-                                 self.token_budget, int(self.use_wt), int(self.use_ut), 0, self.total_pages)
+                                 self.token_budget, int(self.use_wt), int(self.use_ut), int(self.prefix_caching), self.total_pages)
 
 
 _ready = False
@@ -78,6 +80,8 @@ def _lib():
         lib.gllm_sched_destroy.argtypes = [vp]
         lib.gllm_sched_add_request.restype = i32
         lib.gllm_sched_add_request.argtypes = [vp, i64, i32, i32]
+        lib.gllm_sched_add_request_tokens.restype = i32
+        lib.gllm_sched_add_request_tokens.argtypes = [vp, i64, P(i32), i32, i32]
         lib.gllm_sched_next_batch.restype = i32
         lib.gllm_sched_next_batch.argtypes = [vp, P(i64), P(i64), P(i32), P(i32), i32, P(i32)]
         lib.gllm_sched_batch_block_tables.restype = i32
@@ -89,6 +93,9 @@ def _lib():
         lib.gllm_sched_simulate.restype = i32
         lib.gllm_sched_simulate.argtypes = [P(gllm_sched_params), P(gllm_stage_time_model), P(i64), P(i32), P(i32), i64,
                                             P(gllm_sim_result)]
+        lib.gllm_sched_simulate_tokens.restype = i32
+        lib.gllm_sched_simulate_tokens.argtypes = [P(gllm_sched_params), P(gllm_stage_time_model), P(i64), P(i32), P(i32), P(i32),
+                                                   i64, P(gllm_sim_result)]
         _ready = True
     return lib
 
@@ -128,8 +135,15 @@ class Scheduler:
         if st != GLLM_OK:
             raise GllmError(st, what)
 
-    def add_request(self, request_id: int, prompt_len: int, output_len: int) -> None:
-        self._check(self.lib.gllm_sched_add_request(self.handle, request_id, prompt_len, output_len), "gllm_sched_add_request")
+    def add_request(self, request_id: int, prompt_len: int, output_len: int, tokens=None) -> None:
+        if tokens is None:
+            self._check(self.lib.gllm_sched_add_request(self.handle, request_id, prompt_len, output_len), "gllm_sched_add_request")
+        else:
+            t = np.ascontiguousarray(tokens, dtype=np.int32)
+            if t.shape != (prompt_len,):
+                raise ValueError("tokens must hold prompt_len ids")
+            self._check(self.lib.gllm_sched_add_request_tokens(self.handle, request_id, _ptr(t, C.c_int32), prompt_len, output_len),
+                        "gllm_sched_add_request_tokens")
         self._count += 1
 
     def next_batch(self, capacity: Optional[int] = None) -> Optional[Tuple[int, List[Tuple[int, int, int]]]]:
@@ -165,13 +179,20 @@ class Scheduler:
 
 
 def gllm_sched_simulate(params: Params, model: Tuple[int, int, int, int], arrivals) -> dict:
-    """arrivals: sequence of (arrival ns, prompt_len, output_len), ascending in time."""
+    """arrivals: sequence of (arrival ns, prompt_len, output_len[, prompt token ids]), ascending in time."""
     a = np.ascontiguousarray([x[0] for x in arrivals], dtype=np.int64)
     pl = np.ascontiguousarray([x[1] for x in arrivals], dtype=np.int32)
     ol = np.ascontiguousarray([x[2] for x in arrivals], dtype=np.int32)
     cp, cm, res = params.c(), gllm_stage_time_model(*model), gllm_sim_result()
-    st = _lib().gllm_sched_simulate(C.byref(cp), C.byref(cm), _ptr(a, C.c_int64), _ptr(pl, C.c_int32), _ptr(ol, C.c_int32),
-                                    len(a), C.byref(res))
+    if len(arrivals) and len(arrivals[0]) > 3:
+        tk = np.ascontiguousarray(np.concatenate([np.asarray(x[3], dtype=np.int32) for x in arrivals]))
+        if len(tk) != int(pl.sum()):
+            raise ValueError("each prompt must come with prompt_len token ids")
+        st = _lib().gllm_sched_simulate_tokens(C.byref(cp), C.byref(cm), _ptr(a, C.c_int64), _ptr(pl, C.c_int32),
+                                               _ptr(ol, C.c_int32), _ptr(tk, C.c_int32), len(a), C.byref(res))
+    else:
+        st = _lib().gllm_sched_simulate(C.byref(cp), C.byref(cm), _ptr(a, C.c_int64), _ptr(pl, C.c_int32), _ptr(ol, C.c_int32),
+                                        len(a), C.byref(res))
     if st != GLLM_OK:
         raise GllmError(st, "gllm_sched_simulate")
     return {n: int(getattr(res, n)) for n in SIM_FIELDS}

@@ -8,7 +8,7 @@ the CPU oracle nor the HIP library; both are fed the buffers produced here.
 The batches follow the workload structure of the paper: hybrid micro-batches of
 chunked-prefill tokens and single-token decode rows under a 2048-token budget
 (paper section 2.2, "Scheduling Policies", and section 4.1, token budget), paged
-KV with per-sequence page tables shared by every stage (section 3.4), bf16 data
+KV with per-sequence page tables shared by every stage (section 3.3), bf16 data
 (section 4.1), and a PP=4 stage's share of the layers of Llama/Qwen-shaped models.
 The paper's request traces are not used; sequence lengths are drawn from the
 stated distributions instead.

@@ -1,7 +1,7 @@
 """Pins of the scheduling oracle (oracle/throttle_oracle.py) against what the paper fixes: the values of
 Eq. 1, Eq. 2, Eq. 3 and Eq. 4 worked by hand for the paper's hyper-parameters (section 4.1: #T = 8,
 #MaxP = 2048, #MinP = 32, KV_thresh = 0.05), the special cases in which Eq. 3 must reduce to Eq. 1 or Eq. 2,
-the behaviour the two case studies describe in words (sections 3.2 and 3.3), and conservation laws that any
+the behaviour the two case studies describe in words (sections 3.1 and 3.2), and conservation laws that any
 correct scheduler obeys (every request produces exactly its output length, pages are never shared and all come
 back)."""
 import random
