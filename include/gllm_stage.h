@@ -175,7 +175,8 @@ const char* gllm_profile_class_name(int32_t i);
  * (4 wavefronts), 3 = 256x256 (8 wavefronts), 4 = 256x256 tiles for whole rounds of the compute units plus
  * 256x128 tiles for the remainder (only for shapes with such a remainder), 5 = 256x192 (n a multiple of 192,
  * not for SwiGLU), 6 = 128x128 with four LDS stages instead of two (for few rows, where the weights stream
- * from HBM); a forced tile that does not fit the shape gives GLLM_E_UNSUPPORTED. */
+ * from HBM), 7 = 64x128 with three LDS stages (picked up to 64 rows: two workgroups per compute unit keep more
+ * of the weight stream in flight); a forced tile that does not fit the shape gives GLLM_E_UNSUPPORTED. */
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
                               int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream);
 

@@ -18,6 +18,7 @@ constexpr int kPage = 16;        // KV slots per page
 constexpr int kWave = 64;        // lanes per wavefront
 
 // GEMM tile constants that the weight packer and the activation buffers must agree on.
+constexpr int kMaxPlanes = 8;    // split-K partial outputs a consumer kernel can sum
 constexpr int kGemmPadM = 256;   // activation rows are readable up to a multiple of this
 constexpr int kGemmPadN = 256;   // packed weight rows are padded to a multiple of this
 constexpr int kGemmPadK = 64;    // packed weight columns / activation row strides are multiples of this
@@ -33,7 +34,7 @@ enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 // out (op)= a[m x k] * w[n x k]^T, see gllm_op_gemm_bf16 in the public header.
 // tile: -1 picks a tile shape from m and n; 0..3 force one (128x128, 256x128, 256x256, 256x256 with 8 waves);
 // 4 forces the mixed 256x256 + 256x128 launch (only where gemm_mixed_rem_cols(m, n) > 0); 5 = 256x192 (not SwiGLU);
-// 6 = 128x128 with four LDS stages.
+// 6 = 128x128 with four LDS stages; 7 = 64x128 with three LDS stages (up to 64 rows per tile row: weight streaming).
 // splits > 1 (store mode only): split s covers k range [s*k/splits, (s+1)*k/splits) and writes its partial
 // product to out + s*split_stride floats; the consumer sums the planes in order.
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,

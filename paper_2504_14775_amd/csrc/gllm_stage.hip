@@ -38,7 +38,7 @@ struct LayerBuffers {
 };
 
 constexpr int kStagingSlots = 4;
-constexpr int kMaxSplits = 8;
+constexpr int kMaxSplits = kMaxPlanes;
 
 struct MetaLayout {  // offsets in bytes inside the metadata block (host staging and device copy alike)
     size_t tok_pos, tok_page, bt_flat, dec_items, dec_order, dec_rows, pre_items, total;

@@ -333,18 +333,41 @@ __global__ void decode_combine_kernel(AttnArgs a, const DecodeRow* __restrict__ 
                                       const float* __restrict__ part_ml) {
     const DecodeRow rw = rows[blockIdx.x];
     const int hq = blockIdx.y, e = threadIdx.x * 4;
+    // the partials are read eight at a time (all loads of a batch are issued before the first use: a row has a
+    // handful of partials and the kernel is all latency), and combined in partition order
+    constexpr int U = 8;
+    const int64_t slot0 = (int64_t)rw.first_item * a.n_q + hq, slot_step = a.n_q;
     float ms = kNegBig;
-    for (int i = 0; i < rw.num_items; ++i)
-        ms = fmaxf(ms, part_ml[((int64_t)(rw.first_item + i) * a.n_q + hq) * 2]);
+    for (int i0 = 0; i0 < rw.num_items; i0 += U) {
+        float m[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) m[u] = i0 + u < rw.num_items ? part_ml[(slot0 + (i0 + u) * slot_step) * 2] : kNegBig;
+#pragma unroll
+        for (int u = 0; u < U; ++u) ms = fmaxf(ms, m[u]);
+    }
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float ls = 0.f;
-    for (int i = 0; i < rw.num_items; ++i) {
-        const int64_t slot = (int64_t)(rw.first_item + i) * a.n_q + hq;
-        const float sc = __builtin_amdgcn_exp2f(part_ml[slot * 2] - ms);
-        const f32x4 ov = *reinterpret_cast<const f32x4*>(part_o + slot * D + e);
+    for (int i0 = 0; i0 < rw.num_items; i0 += U) {
+        float m[U], l[U];
+        f32x4 ov[U];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[v] += ov[v] * sc;
-        ls += part_ml[slot * 2 + 1] * sc;
+        for (int u = 0; u < U; ++u) {
+            if (i0 + u < rw.num_items) {
+                const int64_t slot = slot0 + (i0 + u) * slot_step;
+                m[u] = part_ml[slot * 2];
+                l[u] = part_ml[slot * 2 + 1];
+                ov[u] = *reinterpret_cast<const f32x4*>(part_o + slot * D + e);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i0 + u < rw.num_items) {
+                const float sc = __builtin_amdgcn_exp2f(m[u] - ms);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] += ov[u][v] * sc;
+                ls += l[u] * sc;
+            }
+        }
     }
     const float inv = 1.0f / ls;
 #pragma unroll

@@ -318,6 +318,7 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 2: return launch_tile<256, 256, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
         case 6: return launch_tile<128, 128, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
+        case 7: return launch_tile<64, 128, 2, 2, MODE, 3>(GLLM_TILE_ARGS);
         case 5:
             if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 4, 2, MODE>(GLLM_TILE_ARGS);
             else return hipErrorInvalidValue;
@@ -366,6 +367,10 @@ int gemm_mixed_rem_cols(int m, int n) {
 // for few rows).  A partial last round of 256x256 tiles that covers at most half of the compute units can be
 // run with half-width tiles instead (mixed launch, ~0.55 of a round).  Split-K multiplies the number of tiles
 // and divides the k-steps, at the price of writing one fp32 plane per split (mostly hidden under other tiles).
+// Up to 64 rows the product is a stream of the weights: a 64x128 tile with three LDS stages (two workgroups per
+// compute unit, 64 KiB of weights in flight on each, half the activation traffic of a 128-row tile) costs
+// 0.30 k_steps per tile, but not less than the weights take at 5.5 TB/s, plus 2; measured 20-35 % faster than
+// every other shape there, so it is the only candidate for such problems and the model only picks its split.
 GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
     const int its = k / BK;
     GemmPlan best{0, 1};
@@ -375,19 +380,20 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
         if (its % s != 0 || (s > 1 && its / s < 8)) continue;
         const double steps = (double)its / s;
         const double plane_cost = (double)m * n * 4.0 * s / 8e12 / 1.65e-6;  // mostly hidden under other tiles
-        if (n % 256 == 0) {
+        const bool skinny = m <= 64 && n % 128 == 0;
+        if (n % 256 == 0 && !skinny) {
             const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 256) * s;
             const bool mixed = s == 1 && gemm_mixed_rem_cols(m, n) > 0;
             const double rounds = mixed ? (double)(tiles / 256) + 0.55 : (double)ceil_div(tiles, 256);
             const double cost = rounds * (steps + 6.0) + plane_cost;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{mixed ? 4 : 3, s}; }
         }
-        if (n % 192 == 0 && mode != GEMM_SWIGLU_BF16) {
+        if (n % 192 == 0 && mode != GEMM_SWIGLU_BF16 && !skinny) {
             const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 192) * s;
             const double cost = (double)ceil_div(tiles, 256) * (steps * 0.88 + 6.0) + plane_cost;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{5, s}; }
         }
-        if (n % 128 == 0) {
+        if (n % 128 == 0 && !skinny) {
             const int64_t tiles = ceil_div(m, 128) * (int64_t)(n / 128) * s;
             const int64_t full = tiles / 512, rem = tiles % 512;
             double cost = (double)full * (steps * 0.70 + 2.3) + plane_cost;
@@ -398,6 +404,12 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
             const bool deep = m <= 256 && tiles <= 256;
             if (deep) cost *= 0.85;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{deep ? 6 : 0, s}; }
+        }
+        if (skinny) {
+            const int64_t tiles = (int64_t)(n / 128) * s;
+            const double stream = (double)n * k * 2.0 / 5.5e12 / 1.65e-6;
+            const double cost = std::max((double)ceil_div(tiles, 512) * steps * 0.30, stream) + 2.0 + plane_cost;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{7, s}; }
         }
     }
     return best;
@@ -420,7 +432,7 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             const double c3 = n % 256 == 0 ? (double)ceil_div(t3, 256) * (steps + 6.0) : 1e30;
             const double c0 = (double)(t0 / 512) * (steps * 0.70 + 2.3) +
                               (t0 % 512 > 256 ? steps * 0.70 + 2.3 : t0 % 512 > 0 ? steps * 0.49 + 2.3 : 0.0);
-            tile = c3 <= c0 ? 3 : (m <= 256 && t0 <= 256) ? 6 : 0;
+            tile = m <= 64 ? 7 : c3 <= c0 ? 3 : (m <= 256 && t0 <= 256) ? 6 : 0;
         }
     }
     if (tile == 4) {  // mixed 256x256 / 256x128 launch

@@ -172,7 +172,7 @@ hipError_t launch_rmsnorm_any(const bf16_t* in, float* x, const float* y, int pl
                               const bf16_t* gamma, bf16_t* h, int64_t ldh, int rows, int hidden, float eps,
                               hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
-    if (hidden % 4 != 0 || hidden > 16 * 1024) return hipErrorInvalidValue;
+    if (hidden % 4 != 0 || hidden > 16 * 1024 || planes < 0 || planes > kMaxPlanes) return hipErrorInvalidValue;
     const int vecs = (int)ceil_div(hidden, 1024);
 #define GLLM_RMS(V) rmsnorm_kernel<FROM_BF16, V><<<rows, 256, 0, stream>>>(in, x, y, planes, plane_stride, gamma, h, ldh, hidden, eps)
     if (vecs <= 1) GLLM_RMS(1);

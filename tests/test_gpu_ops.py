@@ -22,7 +22,7 @@ def padded_rows(bits, rows):
     return out
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6, 7])
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (52, 512, 256), (300, 768, 192), (257, 1280, 704), (1024, 256, 2048)])
 def test_gemm_store_and_add(M, N, K, tile):
     print(f"gemm store/add M={M} N={N} K={K} tile={tile}", flush=True)
@@ -43,7 +43,7 @@ def test_gemm_store_and_add(M, N, K, tile):
     assert np.abs(got2 - 2 * ref).max() <= 4e-5 * scale + 1e-6
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6, 7])
 @pytest.mark.parametrize("M,I,K", [(52, 768, 256), (130, 128, 128), (300, 1408, 320)])
 def test_gemm_swiglu(M, I, K, tile):
     print(f"gemm swiglu M={M} I={I} K={K} tile={tile}", flush=True)
@@ -129,7 +129,7 @@ def test_gemm_mixed_tile_launch(mode, tile):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-4)
 
 
-@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2), (6, 2)])
+@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2), (6, 2), (7, 4)])
 def test_gemm_split_k_planes_sum_to_the_product(tile, splits):
     M, N, K = 300, 512, 1024
     print(f"gemm split-K tile={tile} splits={splits}", flush=True)
