@@ -13,7 +13,7 @@ Prints one JSON line:
   simulation       per policy: last-stage bubble share, spread of micro-batch sizes, mean time to first token,
                    mean end-to-end latency, tokens per second, preemptions -- for a pipeline of 4 equal stages whose
                    stage time follows a linear model fitted to this repository's measured stage kernels at the
-                   70B-shaped configuration.  These are simulated figures, not serving measurements.
+                   70B-shaped configuration (bench_series.py).  These are simulated figures, not serving measurements.
   prefix_caching   the same trace with content: every prompt opens with one of a few shared system prompts.  Native
                    simulation with the page pool's prefix cache (include/gllm_kv.h) on and off; a sample is checked
                    against the oracle's simulation field by field.
@@ -31,10 +31,11 @@ import numpy as np
 
 from paper_2504_14775_amd import sched as S
 
-# stage time model, ns: fitted to bench.py --config llama3_70b_pp4 (20 layers on one MI355X): 33 us per new token
-# (GEMMs and the row-wise kernels), 13.4 ns per cached token a decode row reads, 0.62 ns per (query, key) pair of
-# prefill attention, 0.3 ms fixed
-MODEL = (300_000, 33_000, 13, 632)
+# stage time model, ns: least-squares fit of bench_series.py (16 hybrid batches back to back on the 70B-shaped stage,
+# 20 layers on one MI355X; worst residual 8 %): 9.4 ms fixed (the 34 GB of weights stream once per batch whatever its
+# size), 28.9 us per new token (GEMMs and the row-wise kernels), 11.7 ns per cached token a decode row reads,
+# 0.87 ns per (query, key) pair of prefill attention
+MODEL = (9_400_000, 28_900, 12, 893)
 
 
 def make_trace(n, rate_per_s, seed):
