@@ -1,0 +1,82 @@
+#!/usr/bin/env python3
+"""Closed-loop generation on one GPU: requests -> scheduler -> embedding -> stage -> final norm + vocabulary projection
+-> sampler -> tokens back into the requests (paper_2504_14775_amd/engine.py), with the 8 layers of the Llama-3-8B-shaped
+stage standing for the whole model (hidden 4096, vocabulary 128256, random weights).
+
+    python bench_engine.py [--requests N] [--seed S]
+
+Prints one JSON line.  `value` = generated tokens per second (wall clock, everything included: scheduling, block
+tables, token-id upload, the kernels, the read-back of the sampled ids) with up to #PP_depth micro-batches enqueued ahead;
+`synchronous` repeats the run with one micro-batch in flight, i.e. with the host work exposed; `gpu_busy` is the share
+of the wall time covered by the micro-batches' own event-timed durations.  All requests are present at the start;
+prompt and output lengths are log-normal (medians 220 and 64), a stand-in for a chat workload.
+"""
+import argparse
+import json
+import math
+import random
+import time
+
+import torch
+
+from paper_2504_14775_amd import engine as E
+from paper_2504_14775_amd import sched as S
+from paper_2504_14775_amd import synth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--requests", type=int, default=1024)
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    shape = synth.SHAPES["llama3_8b_pp4"]
+    V, H = 128256, shape.hidden
+    rng = random.Random(args.seed)
+    reqs = []
+    for _ in range(args.requests):
+        p = int(min(2048, max(4, rng.lognormvariate(math.log(220), 0.9))))
+        o = int(min(256, max(1, rng.lognormvariate(math.log(64), 0.6))))
+        reqs.append(([rng.randrange(V) for _ in range(p)], o))
+    layers = [synth.make_layer_weights(shape, args.seed, l, device=dev) for l in range(shape.num_layers)]
+    table = synth.normal_bf16(args.seed, 901, 0, V * H, 1.0, 0.0, device=dev).view(V, H)
+    gain = synth.normal_bf16(args.seed, 902, 0, H, 0.1, 1.0, device=dev)
+    w_vocab = synth.normal_bf16(args.seed, 903, 0, V * H, 0.02, 0.0, device=dev).view(V, H)
+    params = S.Params(policy=S.TOKEN_THROTTLING, iters_t=8, max_p=2048, min_p=32, kv_thresh_bp=500, pp_depth=4,
+                      token_budget=2048, total_pages=32768)
+
+    def run(max_in_flight):
+        eng = E.Engine(shape, V, params, max_batch_tokens=2048 + args.requests, max_batch_seqs=args.requests + 8,
+                       max_context=2048 + 256, device=dev, max_in_flight=max_in_flight, timing=True)
+        eng.load(layers, table, gain, w_vocab)
+        for i, (p, o) in enumerate(reqs):
+            eng.add_request(i, p, o, E.Sampling(temperature=0.8, top_k=50, top_p=0.95, seed=i))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = eng.run()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        st = dict(eng.stats)
+        assert all(len(out[i]) == reqs[i][1] for i in range(len(reqs)))
+        eng.close()
+        return {"generated_tokens_per_s": round(st["tokens_generated"] / wall, 1),
+                "computed_tokens_per_s": round(st["tokens_computed"] / wall, 1), "wall_s": round(wall, 3),
+                "micro_batches": st["micro_batches"], "mean_tokens_per_micro_batch": round(st["tokens_computed"] / st["micro_batches"], 1),
+                "ms_per_micro_batch": round(wall * 1e3 / st["micro_batches"], 3), "gpu_busy": round(st["gpu_ms"] * 1e-3 / wall, 4)}
+
+    run(None)                                               # warm-up: first-use costs of every kernel
+    ahead = run(None)
+    sync = run(1)
+    print(json.dumps({
+        "metric": "generated tokens per second, closed loop on one GPU (scheduler + embedding + stage + head + sampler)",
+        "value": ahead["generated_tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.requests} requests at once, 8 layers of the Llama-3-8B shape as the whole model, vocabulary {V}",
+                   "prompt_tokens": sum(len(p) for p, _ in reqs), "output_tokens": sum(o for _, o in reqs),
+                   "scheduler": "token throttling T=8 MaxP=2048 MinP=32 KV_thresh=0.05 depth=4", "sampling": "temperature 0.8, top-k 50, top-p 0.95"},
+        "enqueued_ahead": ahead, "synchronous": sync}))
+
+
+if __name__ == "__main__":
+    main()

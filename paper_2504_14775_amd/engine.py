@@ -1,0 +1,230 @@
+"""A serving loop on one GPU around the library's pieces: scheduler -> embedding -> stage -> final norm + vocabulary
+projection -> sampler, the sampled tokens going back into the requests.
+
+One pipeline stage holds the whole model here (one GPU), so what is shown of the paper's runtime (arxiv 2504.14775,
+section 3.3) is its asynchronous side: up to #PP_depth micro-batches are enqueued before the oldest one is waited
+for, so the host work of a micro-batch (scheduling, block tables, token ids: the "metadata") runs while the GPU
+executes the micro-batches before it; only the sampled token ids travel back.  This module does no arithmetic on
+activations: every step of the path is a call into the C ABI (binding.py, sched.py, head.py).
+"""
+from __future__ import annotations
+
+from collections import deque
+from dataclasses import dataclass, field
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import binding, head, sched, synth
+
+PAGE = 16
+
+
+@dataclass
+class Sampling:
+    temperature: float = 0.0     # <= 0: greedy
+    top_k: int = 0               # 0: no limit
+    top_p: float = 1.0
+    seed: int = 0
+
+
+@dataclass
+class _Request:
+    tokens: List[int]            # prompt, then every token generated so far
+    prompt_len: int
+    max_new: int
+    sampling: Sampling
+    rng: np.random.Generator
+    done: bool = False
+
+
+@dataclass
+class _Slot:
+    """Buffers of one micro-batch in flight."""
+    ids_host: object
+    ids: object
+    x: object
+    out: object
+    out32: object
+    sel_host: object
+    sel: object
+    par_host: object             # [3, max_seqs] float32: temperature, top_p, u
+    top_k_host: object
+    temp: object
+    top_k: object
+    top_p: object
+    u: object
+    logits: object
+    picked: object
+    picked_host: object
+    event: object
+    begin: object                # timed event in front of the micro-batch (timing mode)
+    batch_id: int = -1
+    rows: List[Tuple[int, int, int]] = field(default_factory=list)
+    takers: List[int] = field(default_factory=list)
+    num_tokens: int = 0
+
+
+class Engine:
+    def __init__(self, shape: synth.StageShape, vocab: int, params: sched.Params, *, max_batch_tokens: int,
+                 max_batch_seqs: int, max_context: int, device: str = "cuda", max_in_flight: Optional[int] = None,
+                 timing: bool = False):
+        """max_in_flight: micro-batches enqueued before the oldest is waited for (default and at most #PP_depth;
+        1 makes the loop synchronous).  timing: bracket every micro-batch with timed events (stats["gpu_ms"])."""
+        import torch
+        self.torch = torch
+        self.shape, self.vocab, self.params, self.device = shape, vocab, params, device
+        self.max_tokens, self.max_seqs, self.max_context = max_batch_tokens, max_batch_seqs, max_context
+        self.max_blocks = -(-max_context // PAGE)
+        self.sched = sched.Scheduler(params)
+        self.stage = binding.Stage(binding.make_config(shape, max_batch_tokens, max_batch_seqs, self.max_blocks, max_context))
+        self._ws = torch.empty(self.stage.workspace_bytes(), dtype=torch.uint8, device=device)
+        self.stage.bind_workspace(self._ws)
+        self.head = head.Head(shape.hidden, vocab, max_batch_seqs, shape.rms_eps, device=device)
+        n_el = shape.num_layers * synth.pool_elems_per_layer(shape, params.total_pages)
+        self.k_pool = torch.zeros(n_el, dtype=torch.bfloat16, device=device)
+        self.v_pool = torch.zeros(n_el, dtype=torch.bfloat16, device=device)
+        self.stage.bind_kv_pool(self.k_pool, self.v_pool, params.total_pages)
+        self.table = None
+        self.requests: Dict[int, _Request] = {}
+        self.flying: deque = deque()
+        self.timing = timing
+        depth = params.pp_depth if max_in_flight is None else max(1, min(max_in_flight, params.pp_depth))
+        self.free_slots = [self._make_slot() for _ in range(depth)]
+        self.observer: Optional[Callable] = None     # tests: called with the slot of every retired micro-batch
+        self.stats = {"micro_batches": 0, "tokens_computed": 0, "tokens_generated": 0, "gpu_ms": 0.0}
+
+    def _make_slot(self) -> _Slot:
+        t, dev, H = self.torch, self.device, self.shape.hidden
+        T, S = self.max_tokens, self.max_seqs
+        pin = lambda *shape, dtype: t.empty(*shape, dtype=dtype, pin_memory=True)
+        return _Slot(
+            ids_host=pin(T, dtype=t.int32), ids=t.empty(T, dtype=t.int32, device=dev),
+            x=t.empty(T, H, dtype=t.bfloat16, device=dev), out=t.empty(T, H, dtype=t.bfloat16, device=dev),
+            out32=t.empty(T, H, dtype=t.float32, device=dev),
+            sel_host=pin(S, dtype=t.int32), sel=t.empty(S, dtype=t.int32, device=dev),
+            par_host=pin(3, S, dtype=t.float32), top_k_host=pin(S, dtype=t.int32), temp=t.empty(S, dtype=t.float32, device=dev),
+            top_k=t.empty(S, dtype=t.int32, device=dev), top_p=t.empty(S, dtype=t.float32, device=dev),
+            u=t.empty(S, dtype=t.float32, device=dev),
+            logits=t.empty(S, self.head.padded_vocab, dtype=t.float32, device=dev),
+            picked=t.empty(S, dtype=t.int32, device=dev), picked_host=pin(S, dtype=t.int32),
+            event=t.cuda.Event(enable_timing=self.timing), begin=t.cuda.Event(enable_timing=True) if self.timing else None)
+
+    # ---- set-up -----------------------------------------------------------------------------------------------
+    def load(self, layers: Sequence[Dict[str, object]], embedding_table, final_norm_gain, w_vocab) -> None:
+        """layers: per layer the device tensors gllm_stage_load_layer takes; embedding_table: bf16 [vocab, hidden];
+        final_norm_gain: bf16 [hidden]; w_vocab: bf16 [vocab, hidden].  The table is used in place (keep it alive)."""
+        for l, w in enumerate(layers):
+            self.stage.load_layer(l, w)
+        self.head.load(final_norm_gain, w_vocab)
+        self.table = embedding_table
+        self.torch.cuda.synchronize()
+
+    def add_request(self, request_id: int, prompt: Sequence[int], max_new_tokens: int, sampling: Optional[Sampling] = None) -> None:
+        if len(prompt) + max_new_tokens > self.max_context:
+            raise ValueError("prompt + max_new_tokens exceeds max_context")
+        sp = sampling or Sampling()
+        self.sched.add_request(request_id, len(prompt), max_new_tokens,
+                               tokens=list(prompt) if self.params.prefix_caching else None)
+        self.requests[request_id] = _Request(list(prompt), len(prompt), max_new_tokens, sp, np.random.default_rng(sp.seed))
+
+    # ---- the loop ---------------------------------------------------------------------------------------------
+    def _launch(self) -> bool:
+        """Schedules one micro-batch and enqueues all of its GPU work; False when nothing could be scheduled."""
+        if not self.free_slots:
+            return False
+        got = self.sched.next_batch()
+        if got is None:
+            return False
+        t = self.torch
+        bid, rows = got
+        nt = np.fromiter((n for _, n, _ in rows), dtype=np.int32, count=len(rows))
+        cl = np.fromiter((c for _, _, c in rows), dtype=np.int32, count=len(rows))
+        T = int(nt.sum())
+        if T > self.max_tokens or len(rows) > self.max_seqs:
+            raise RuntimeError(f"micro-batch of {T} tokens / {len(rows)} rows exceeds the engine's sizes")
+        bt = self.sched.block_tables(bid, len(rows), self.max_blocks)
+        slot = self.free_slots.pop()
+        ids = slot.ids_host.numpy()
+        at = 0
+        takers = []
+        for i, (rid, n, c) in enumerate(rows):
+            r = self.requests[rid]
+            ids[at:at + n] = r.tokens[c:c + n]
+            at += n
+            if c + n == len(r.tokens):                     # the row's last token is the newest one: it yields the next
+                takers.append(i)
+        m = len(takers)
+        if m:
+            ends = np.cumsum(nt) - 1
+            slot.sel_host.numpy()[:m] = ends[takers]
+            par, top_k = slot.par_host.numpy(), slot.top_k_host.numpy()
+            for j, i in enumerate(takers):
+                r = self.requests[rows[i][0]]
+                par[0, j], par[1, j], top_k[j] = r.sampling.temperature, r.sampling.top_p, r.sampling.top_k
+                par[2, j] = r.rng.random(dtype=np.float32) if r.sampling.temperature > 0 else 0.0
+        if self.timing:
+            slot.begin.record()
+        slot.ids[:T].copy_(slot.ids_host[:T], non_blocking=True)
+        head.gllm_op_embedding(slot.ids[:T], self.table, slot.x[:T])
+        self.stage.forward(nt, cl, bt, slot.x, slot.out, slot.out32)
+        if m:
+            slot.sel[:m].copy_(slot.sel_host[:m], non_blocking=True)
+            slot.temp[:m].copy_(slot.par_host[0, :m], non_blocking=True)
+            slot.top_k[:m].copy_(slot.top_k_host[:m], non_blocking=True)
+            slot.top_p[:m].copy_(slot.par_host[1, :m], non_blocking=True)
+            slot.u[:m].copy_(slot.par_host[2, :m], non_blocking=True)
+            self.head.logits(slot.out32[:T], slot.sel[:m], slot.logits[:m])
+            head.gllm_op_sample(slot.logits[:m], self.vocab, slot.temp[:m], slot.top_k[:m], slot.top_p[:m], slot.u[:m], slot.picked[:m])
+            slot.picked_host[:m].copy_(slot.picked[:m], non_blocking=True)
+        slot.event.record()
+        slot.batch_id, slot.rows, slot.takers, slot.num_tokens = bid, rows, takers, T
+        self.flying.append(slot)
+        self.stats["micro_batches"] += 1
+        self.stats["tokens_computed"] += T
+        return True
+
+    def _retire(self) -> List[Tuple[int, int, bool]]:
+        """Waits for the oldest micro-batch; returns (request id, new token, request ended) per token it produced."""
+        slot = self.flying.popleft()
+        slot.event.synchronize()
+        if self.timing:
+            self.stats["gpu_ms"] += slot.begin.elapsed_time(slot.event)
+        picked = slot.picked_host.numpy()
+        news = []
+        for j, i in enumerate(slot.takers):
+            rid = slot.rows[i][0]
+            self.requests[rid].tokens.append(int(picked[j]))
+            news.append(rid)
+        if self.observer is not None:
+            self.observer(slot)
+        ended = set(self.sched.complete_batch(slot.batch_id))
+        for rid in ended:
+            self.requests[rid].done = True
+        self.stats["tokens_generated"] += len(news)
+        self.free_slots.append(slot)
+        return [(rid, self.requests[rid].tokens[-1], rid in ended) for rid in news]
+
+    def step(self) -> List[Tuple[int, int, bool]]:
+        """Enqueues micro-batches while the scheduler yields some and the pipeline has room, then retires the oldest
+        one.  Returns the tokens that became known; empty when nothing is in flight and nothing can be scheduled."""
+        while self._launch():
+            pass
+        return self._retire() if self.flying else []
+
+    def run(self) -> Dict[int, List[int]]:
+        """Runs until every request has ended; returns the generated tokens per request id."""
+        while any(not r.done for r in self.requests.values()):
+            launched = False
+            while self._launch():
+                launched = True
+            if self.flying:
+                self._retire()
+            elif not launched:
+                raise RuntimeError("the scheduler cannot make progress (pool too small for the oldest request?)")
+        return {rid: r.tokens[r.prompt_len:] for rid, r in self.requests.items()}
+
+    def close(self) -> None:
+        self.torch.cuda.synchronize()
+        self.head.destroy()
+        self.stage.destroy()
