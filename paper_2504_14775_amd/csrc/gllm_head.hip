@@ -75,11 +75,56 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const bf16_t* __restrict_
 constexpr int kSampleThreads = 1024;
 constexpr int kSampleWaves = kSampleThreads / 64;
 constexpr int kCompact = 1024;
+constexpr int kList = 4096;  // top-k candidates held in LDS while the k-th largest is selected among them
 
 // order-preserving map from float to unsigned: a < b  <=>  key(a) < key(b) (for non-NaN values)
 __device__ __forceinline__ uint32_t float_key(float f) {
     const uint32_t b = __float_as_uint(f);
     return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+// Calls f(index, logit) for the elements of a row that this thread owns, in increasing index order: groups of four
+// consecutive logits (16-byte loads, two in flight) when the row starts on a 16-byte boundary, single ones otherwise.
+template <class F>
+__device__ __forceinline__ void for_row(const float* __restrict__ lg, int vocab, F&& f) {
+    const int tid = threadIdx.x;
+    if ((reinterpret_cast<uintptr_t>(lg) & 15) == 0) {
+        const int groups = vocab >> 2;
+        int g = tid;
+        for (; g + kSampleThreads < groups; g += 2 * kSampleThreads) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(lg + 4 * g);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(lg + 4 * (g + kSampleThreads));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f(4 * g + e, a[e]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f(4 * (g + kSampleThreads) + e, b[e]);
+        }
+        if (g < groups) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(lg + 4 * g);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f(4 * g + e, a[e]);
+        }
+        const int t = 4 * groups + tid;
+        if (t < vocab) f(t, lg[t]);
+    } else {
+        for (int i = tid; i < vocab; i += kSampleThreads) f(i, lg[i]);
+    }
+}
+
+// hist[bin] += 1 for every lane with `on`.  Lanes of a wave that hit the same bin are counted together (the top
+// byte of the keys takes two or three values in a whole row, and same-address LDS atomics run one after the
+// other); after three such rounds the rest adds singly (many different bins: those run in parallel).
+__device__ __forceinline__ void hist_add(unsigned* hist, bool on, uint32_t bin) {
+    const int lane = threadIdx.x & 63;
+    uint64_t todo = __ballot(on);
+    for (int round = 0; round < 3 && todo; ++round) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t b = (uint32_t)__shfl((int)bin, leader);
+        const uint64_t same = __ballot(on && bin == b) & todo;
+        if (lane == leader) atomicAdd(&hist[b], (unsigned)__popcll(same));
+        todo &= ~same;
+    }
+    if ((todo >> lane) & 1) atomicAdd(&hist[bin], 1u);
 }
 
 // Sum over the workgroup with a fixed association (lanes by butterfly, then the 16 wave sums in order), so that a
@@ -113,21 +158,30 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
     __shared__ float fs[kSampleThreads];   // reductions; later the probabilities of the compact list
     __shared__ int is[kSampleThreads];     // reductions; later the token ids of the compact list
     __shared__ unsigned hist[256];
+    __shared__ uint32_t list_key[kList];   // key(z) and token id of the top-k candidates
+    __shared__ int list_id[kList];
     __shared__ uint32_t sh_key;
     __shared__ int sh_int;
     const int tid = threadIdx.x, row = blockIdx.x;
     const float* lg = logits + (int64_t)row * ld;
 
-    // pass 1: the largest logit and its lowest index (greedy; also the softmax reference)
+    const float temp = temperature[row];
+    const int k = top_k[row];
+    const bool select = temp > 0.f && k > 0 && k < vocab;  // top-k is on: the first pass also counts top bytes
+
+    // pass 1: the largest logit and its lowest index (greedy; also the softmax reference); with top-k, the
+    // histogram of the top byte of the logits' own keys (dividing by the temperature keeps their order)
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
     float best = -INFINITY;
     int best_i = INT_MAX;
-    for (int i = tid; i < vocab; i += kSampleThreads) {
-        const float v = lg[i];
+    for_row(lg, vocab, [&](int i, float v) {
         if (v > best) {
             best = v;
             best_i = i;
         }
-    }
+        if (select) hist_add(hist, true, float_key(v) >> 24);
+    });
     fs[tid] = best;
     is[tid] = best_i;
     __syncthreads();
@@ -145,7 +199,6 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
     best = fs[0];
     best_i = is[0] == INT_MAX ? 0 : is[0];
     __syncthreads();
-    const float temp = temperature[row];
     if (!(temp > 0.f)) {
         if (tid == 0) out[row] = best_i;
         return;
@@ -154,53 +207,160 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
     const float p = top_p[row];
     const float u = uniform[row];
 
-    // top-k: the k-th largest key by a radix select over the four bytes of the key, most significant first;
-    // tokens with key >= floor_key are kept (all of them when top-k is off)
+    // The bin that holds the want-th largest entry of the 256-bin histogram goes to sh_key (bin 0 when there are
+    // fewer entries than that), the number of entries above that bin to sh_int, the bin's own count to hist[0].
+    // Wave 0 does it: lane l owns bins 4l .. 4l+3, a shuffle scan gives the count above each lane's bins.
+    auto pick_bin = [&](int want) {
+        if (tid < 64) {
+            int c[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[j] = (int)hist[4 * tid + j];
+            const int mine = c[0] + c[1] + c[2] + c[3];
+            int incl = mine;  // entries in this lane's bins and all higher ones
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int other = __shfl_down(incl, o);
+                if (tid + o < 64) incl += other;
+            }
+            int above = incl - mine, found = -1, found_above = 0;
+#pragma unroll
+            for (int j = 3; j >= 0; --j) {
+                if (found < 0 && above + c[j] >= want && 4 * tid + j > 0) {
+                    found = 4 * tid + j;
+                    found_above = above;
+                }
+                above += c[j];
+            }
+            // the highest bin that qualifies wins; lane 0 reports bin 0 when none does
+            const uint64_t have = __ballot(found >= 0);
+            const int winner = have ? 63 - __clzll((long long)have) : 0;
+            if (tid == winner) {
+                const int bin = have ? found : 0;
+                sh_key = (uint32_t)bin;
+                sh_int = have ? found_above : incl - c[0];
+                hist[0] = hist[bin];
+            }
+        }
+        __syncthreads();
+    };
+
+    // top-k: tokens with key(z) >= floor_key are kept, z = logit / temperature (all of them when top-k is off)
     uint32_t floor_key = 0;
     int kept = vocab;
-    const int k = top_k[row];
-    if (k > 0 && k < vocab) {
-        uint32_t prefix = 0;
-        int want = k, above_total = 0;
-        for (int byte = 3; byte >= 0; --byte) {
-            if (tid < 256) hist[tid] = 0;
+    bool listed = false;  // is[0 .. sh_int) already holds the ids of the kept tokens
+    if (select) {
+        // Two more bytes would cost two more passes over the row.  Instead: one pass for the second byte, then
+        // every token whose logit key is at or above the 16-bit prefix of the k-th largest goes into a short
+        // list in LDS (with its exact key(z)), and the k-th largest z is selected on that list.  The list is taken
+        // by z, not by logit -- z >= (smallest logit of the prefix) / temperature -- so tokens whose z ties with a
+        // listed one are listed too, whatever their logit.
+        pick_bin(k);
+        const uint32_t b3 = sh_key;
+        const int above3 = sh_int;
+        __syncthreads();
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for_row(lg, vocab, [&](int, float v) {
+            const uint32_t key = float_key(v);
+            hist_add(hist, (key >> 24) == b3, (key >> 16) & 255u);
+        });
+        __syncthreads();
+        pick_bin(k - above3);
+        const uint32_t prefix16 = (b3 << 8) | sh_key;
+        const int candidates = above3 + sh_int + (int)hist[0];
+        __syncthreads();
+        bool done = false;
+        if (candidates <= kList) {
+            const uint32_t edge_key = prefix16 << 16;  // smallest key with that prefix; back to the float it encodes
+            const float edge = __uint_as_float((edge_key & 0x80000000u) ? edge_key ^ 0x80000000u : ~edge_key);
+            const uint32_t edge_z = float_key(edge / temp);
+            if (tid == 0) sh_int = 0;
             __syncthreads();
-            const int shift = byte * 8;
-            const uint32_t high_mask = byte == 3 ? 0u : 0xFFFFFFFFu << (shift + 8);
-            for (int i = tid; i < vocab; i += kSampleThreads) {
-                const uint32_t key = float_key(lg[i] / temp);
-                if ((key & high_mask) == (prefix & high_mask)) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            for_row(lg, vocab, [&](int i, float v) {
+                const uint32_t zk = float_key(v / temp);
+                if (zk >= edge_z) {
+                    const int slot = atomicAdd(&sh_int, 1);
+                    if (slot < kList) {
+                        list_key[slot] = zk;
+                        list_id[slot] = i;
+                    }
+                }
+            });
+            __syncthreads();
+            const int n_list = sh_int;
+            __syncthreads();
+            if (n_list <= kList) {  // (ties in z can add entries beyond the count taken on logits)
+                // radix select of the k-th largest key(z) on the list, most significant byte first
+                uint32_t prefix = 0;
+                int want = k, above_total = 0;
+                for (int byte = 3; byte >= 0; --byte) {
+                    if (tid < 256) hist[tid] = 0;
+                    __syncthreads();
+                    const int shift = byte * 8;
+                    const uint32_t high_mask = byte == 3 ? 0u : 0xFFFFFFFFu << (shift + 8);
+                    for (int j = tid; j < n_list; j += kSampleThreads) {
+                        const uint32_t key = list_key[j];
+                        if ((key & high_mask) == (prefix & high_mask)) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                    }
+                    __syncthreads();
+                    pick_bin(want);
+                    prefix |= sh_key << shift;
+                    want -= sh_int;
+                    above_total += sh_int;
+                    if (byte == 0) kept = above_total + (int)hist[0];
+                    __syncthreads();
+                }
+                floor_key = prefix;
+                done = true;
+                if (kept <= kCompact) {
+                    if (tid == 0) sh_int = 0;
+                    __syncthreads();
+                    for (int j = tid; j < n_list; j += kSampleThreads)
+                        if (list_key[j] >= floor_key) is[atomicAdd(&sh_int, 1)] = list_id[j];
+                    __syncthreads();
+                    listed = true;
+                }
             }
-            __syncthreads();
-            if (tid == 0) {
-                int bin = 255, above = 0;
-                while (bin > 0 && above + (int)hist[bin] < want) above += (int)hist[bin--];
-                sh_key = prefix | ((uint32_t)bin << shift);
-                sh_int = above;
-                hist[0] = hist[bin];  // tokens that share the chosen byte (all equal to the k-th once byte 0 is done)
-            }
-            __syncthreads();
-            prefix = sh_key;
-            want -= sh_int;
-            above_total += sh_int;
-            if (byte == 0) kept = above_total + (int)hist[0];
-            __syncthreads();
         }
-        floor_key = prefix;
+        if (!done) {
+            // many near-equal logits around the k-th largest: radix select over the four bytes of key(z) on the
+            // whole row, one pass per byte
+            uint32_t prefix = 0;
+            int want = k, above_total = 0;
+            for (int byte = 3; byte >= 0; --byte) {
+                if (tid < 256) hist[tid] = 0;
+                __syncthreads();
+                const int shift = byte * 8;
+                const uint32_t high_mask = byte == 3 ? 0u : 0xFFFFFFFFu << (shift + 8);
+                for_row(lg, vocab, [&](int, float v) {
+                    const uint32_t key = float_key(v / temp);
+                    hist_add(hist, (key & high_mask) == (prefix & high_mask), (key >> shift) & 255u);
+                });
+                __syncthreads();
+                pick_bin(want);
+                prefix |= sh_key << shift;
+                want -= sh_int;
+                above_total += sh_int;
+                if (byte == 0) kept = above_total + (int)hist[0];
+                __syncthreads();
+            }
+            floor_key = prefix;
+        }
     }
 
     if (kept <= kCompact) {
-        // ---- short list: gather (probability, id), order by id, nucleus and draw on the list ----
-        if (tid == 0) sh_int = 0;
-        __syncthreads();
-        for (int i = tid; i < vocab; i += kSampleThreads) {
-            const float z = lg[i] / temp;
-            if (float_key(z) >= floor_key) {
-                const int slot = atomicAdd(&sh_int, 1);
-                is[slot] = i;
-            }
+        // ---- short list: gather the ids, order by id, nucleus and draw on the list ----
+        if (!listed) {
+            if (tid == 0) sh_int = 0;
+            __syncthreads();
+            for_row(lg, vocab, [&](int i, float v) {
+                if (float_key(v / temp) >= floor_key) {
+                    const int slot = atomicAdd(&sh_int, 1);
+                    is[slot] = i;
+                }
+            });
+            __syncthreads();
         }
-        __syncthreads();
         const int n = sh_int;
         // bitonic sort of the ids (padding sorts last): the list is in index order whatever order the atomics took
         if (tid >= n) is[tid] = INT_MAX;
@@ -268,13 +428,13 @@ __global__ __launch_bounds__(kSampleThreads) void sample_kernel(const float* __r
     auto masses = [&](const uint32_t (&from)[15], float (&m)[15]) {  // m[j] = sum of exp(z - zmax) over key >= from[j]
 #pragma unroll
         for (int j = 0; j < 15; ++j) m[j] = 0.f;
-        for (int i = tid; i < vocab; i += kSampleThreads) {
-            const float z = lg[i] / temp;
+        for_row(lg, vocab, [&](int, float v) {
+            const float z = v / temp;
             const uint32_t key = float_key(z);
             const float e = __expf(z - zmax);
 #pragma unroll
             for (int j = 0; j < 15; ++j) m[j] += key >= from[j] ? e : 0.f;
-        }
+        });
         block_sums(m, fs);
     };
     uint32_t probe[15];

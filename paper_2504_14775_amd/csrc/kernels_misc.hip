@@ -25,8 +25,10 @@ __device__ __forceinline__ float block_sum_256(float v, float* red /*[4]*/) {
 // One workgroup per row.  FROM_BF16: the row comes from the bf16 stage input and is also written out
 // as the fp32 residual stream.  Otherwise the row is the fp32 residual stream plus `planes` partial
 // GEMM outputs (summed in plane order and written back), so the residual add costs no extra pass.
-// The row is kept in registers between the two phases (MAXV 16-byte pieces per thread).
-template <bool FROM_BF16, int MAXV>
+// The row is kept in registers between the two phases (MAXV 16-byte pieces per thread).  PLANES >= 0 fixes the
+// number of planes at compile time (the loop unrolls and all loads of a piece are issued together: with a few
+// hundred rows the kernel is all latency); PLANES < 0 takes it from the argument.
+template <bool FROM_BF16, int MAXV, int PLANES>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t* __restrict__ in, float* __restrict__ x,
                                                        const float* __restrict__ y, int planes, int64_t plane_stride,
                                                        const bf16_t* __restrict__ gamma, bf16_t* __restrict__ h,
@@ -46,8 +48,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t* __restrict__
                 *reinterpret_cast<f32x4*>(xr + j) = v;
             } else {
                 v = *reinterpret_cast<const f32x4*>(xr + j);
-                for (int p = 0; p < planes; ++p)
-                    v += *reinterpret_cast<const f32x4*>(y + p * plane_stride + row * hidden + j);
+                if constexpr (PLANES >= 0) {
+                    f32x4 part[PLANES > 0 ? PLANES : 1];
+#pragma unroll
+                    for (int p = 0; p < PLANES; ++p)
+                        part[p] = *reinterpret_cast<const f32x4*>(y + p * plane_stride + row * hidden + j);
+#pragma unroll
+                    for (int p = 0; p < PLANES; ++p) v += part[p];
+                } else {
+                    for (int p = 0; p < planes; ++p)
+                        v += *reinterpret_cast<const f32x4*>(y + p * plane_stride + row * hidden + j);
+                }
                 if (planes > 0) *reinterpret_cast<f32x4*>(xr + j) = v;
             }
         }
@@ -174,7 +185,16 @@ hipError_t launch_rmsnorm_any(const bf16_t* in, float* x, const float* y, int pl
     if (rows <= 0) return hipSuccess;
     if (hidden % 4 != 0 || hidden > 16 * 1024 || planes < 0 || planes > kMaxPlanes) return hipErrorInvalidValue;
     const int vecs = (int)ceil_div(hidden, 1024);
-#define GLLM_RMS(V) rmsnorm_kernel<FROM_BF16, V><<<rows, 256, 0, stream>>>(in, x, y, planes, plane_stride, gamma, h, ldh, hidden, eps)
+#define GLLM_RMS_P(V, P) rmsnorm_kernel<FROM_BF16, V, P><<<rows, 256, 0, stream>>>(in, x, y, planes, plane_stride, gamma, h, ldh, hidden, eps)
+#define GLLM_RMS(V)                                              \
+    do {                                                         \
+        if (FROM_BF16 || planes == 0) GLLM_RMS_P(V, 0);          \
+        else if (planes == 1) GLLM_RMS_P(V, 1);                  \
+        else if (planes == 2) GLLM_RMS_P(V, 2);                  \
+        else if (planes == 4) GLLM_RMS_P(V, 4);                  \
+        else if (planes == 8) GLLM_RMS_P(V, 8);                  \
+        else GLLM_RMS_P(V, -1);                                  \
+    } while (0)
     if (vecs <= 1) GLLM_RMS(1);
     else if (vecs <= 2) GLLM_RMS(2);
     else if (vecs <= 4) GLLM_RMS(4);
@@ -182,6 +202,7 @@ hipError_t launch_rmsnorm_any(const bf16_t* in, float* x, const float* y, int pl
     else if (vecs <= 8) GLLM_RMS(8);
     else GLLM_RMS(16);
 #undef GLLM_RMS
+#undef GLLM_RMS_P
     return hipGetLastError();
 }
 

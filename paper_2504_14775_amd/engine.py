@@ -46,14 +46,8 @@ class _Slot:
     x: object
     out: object
     out32: object
-    sel_host: object
-    sel: object
-    par_host: object             # [3, max_seqs] float32: temperature, top_p, u
-    top_k_host: object
-    temp: object
-    top_k: object
-    top_p: object
-    u: object
+    par_host: object             # pinned [5, max_seqs] 32-bit words: selected rows, top_k (int32), temperature, top_p, u (float32)
+    par: object                  # the same on the device: one copy per micro-batch
     logits: object
     picked: object
     picked_host: object
@@ -102,10 +96,7 @@ class Engine:
             ids_host=pin(T, dtype=t.int32), ids=t.empty(T, dtype=t.int32, device=dev),
             x=t.empty(T, H, dtype=t.bfloat16, device=dev), out=t.empty(T, H, dtype=t.bfloat16, device=dev),
             out32=t.empty(T, H, dtype=t.float32, device=dev),
-            sel_host=pin(S, dtype=t.int32), sel=t.empty(S, dtype=t.int32, device=dev),
-            par_host=pin(3, S, dtype=t.float32), top_k_host=pin(S, dtype=t.int32), temp=t.empty(S, dtype=t.float32, device=dev),
-            top_k=t.empty(S, dtype=t.int32, device=dev), top_p=t.empty(S, dtype=t.float32, device=dev),
-            u=t.empty(S, dtype=t.float32, device=dev),
+            par_host=pin(5, S, dtype=t.int32).zero_(), par=t.zeros(5, S, dtype=t.int32, device=dev),
             logits=t.empty(S, self.head.padded_vocab, dtype=t.float32, device=dev),
             picked=t.empty(S, dtype=t.int32, device=dev), picked_host=pin(S, dtype=t.int32),
             event=t.cuda.Event(enable_timing=self.timing), begin=t.cuda.Event(enable_timing=True) if self.timing else None)
@@ -157,25 +148,25 @@ class Engine:
         m = len(takers)
         if m:
             ends = np.cumsum(nt) - 1
-            slot.sel_host.numpy()[:m] = ends[takers]
-            par, top_k = slot.par_host.numpy(), slot.top_k_host.numpy()
+            words = slot.par_host.numpy()
+            reals = words.view(np.float32)
+            words[0, :m] = ends[takers]
             for j, i in enumerate(takers):
                 r = self.requests[rows[i][0]]
-                par[0, j], par[1, j], top_k[j] = r.sampling.temperature, r.sampling.top_p, r.sampling.top_k
-                par[2, j] = r.rng.random(dtype=np.float32) if r.sampling.temperature > 0 else 0.0
+                words[1, j] = r.sampling.top_k
+                reals[2, j], reals[3, j] = r.sampling.temperature, r.sampling.top_p
+                reals[4, j] = r.rng.random(dtype=np.float32) if r.sampling.temperature > 0 else 0.0
         if self.timing:
             slot.begin.record()
         slot.ids[:T].copy_(slot.ids_host[:T], non_blocking=True)
         head.gllm_op_embedding(slot.ids[:T], self.table, slot.x[:T])
         self.stage.forward(nt, cl, bt, slot.x, slot.out, slot.out32)
         if m:
-            slot.sel[:m].copy_(slot.sel_host[:m], non_blocking=True)
-            slot.temp[:m].copy_(slot.par_host[0, :m], non_blocking=True)
-            slot.top_k[:m].copy_(slot.top_k_host[:m], non_blocking=True)
-            slot.top_p[:m].copy_(slot.par_host[1, :m], non_blocking=True)
-            slot.u[:m].copy_(slot.par_host[2, :m], non_blocking=True)
-            self.head.logits(slot.out32[:T], slot.sel[:m], slot.logits[:m])
-            head.gllm_op_sample(slot.logits[:m], self.vocab, slot.temp[:m], slot.top_k[:m], slot.top_p[:m], slot.u[:m], slot.picked[:m])
+            slot.par.copy_(slot.par_host, non_blocking=True)
+            reals_dev = slot.par.view(t.float32)
+            self.head.logits(slot.out32[:T], slot.par[0, :m], slot.logits[:m])
+            head.gllm_op_sample(slot.logits[:m], self.vocab, reals_dev[2, :m], slot.par[1, :m], reals_dev[3, :m], reals_dev[4, :m],
+                                slot.picked[:m])
             slot.picked_host[:m].copy_(slot.picked[:m], non_blocking=True)
         slot.event.record()
         slot.batch_id, slot.rows, slot.takers, slot.num_tokens = bid, rows, takers, T
