@@ -124,6 +124,9 @@ __global__ __launch_bounds__(256) void pack_gate_up_kernel(const bf16_t* __restr
 // bf16 and stored at (page, slot = pos % 16) in the layer's pool:
 //   K element (head h, dim e) -> ((page*n_kv + h)*d*16) + (e/8)*128 + slot*8 + e%8
 //   V element (head h, dim e) -> ((page*n_kv + h)*d*16) + e*16 + slot
+// PLANES >= 1 fixes the number of split-K planes at compile time (their loads are then issued together), PLANES < 0
+// takes it from the arguments.
+template <int PLANES>
 __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
     const int t = blockIdx.x;
     const int d = a.d, half = d / 2, hq = half / 4;  // a thread handles 4 consecutive pairs
@@ -136,7 +139,15 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
     const int k_col0 = a.n_q * d, v_col0 = k_col0 + a.n_kv * d;
     auto gather = [&](int col) {  // sum of the partial planes (+ bias) of 4 consecutive columns
         f32x4 v = *reinterpret_cast<const f32x4*>(row + col);
-        for (int p = 1; p < a.planes; ++p) v += *reinterpret_cast<const f32x4*>(row + p * a.plane_stride + col);
+        if constexpr (PLANES >= 1) {
+            f32x4 part[PLANES];
+#pragma unroll
+            for (int p = 1; p < PLANES; ++p) part[p] = *reinterpret_cast<const f32x4*>(row + p * a.plane_stride + col);
+#pragma unroll
+            for (int p = 1; p < PLANES; ++p) v += part[p];
+        } else {
+            for (int p = 1; p < a.planes; ++p) v += *reinterpret_cast<const f32x4*>(row + p * a.plane_stride + col);
+        }
         if (a.bias) v += __builtin_convertvector(*reinterpret_cast<const bf16x4*>(a.bias + col), f32x4);
         return v;
     };
@@ -242,6 +253,12 @@ hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, 
 
 hipError_t launch_rope_kv_write(const RopeKvArgs& a, hipStream_t stream) {
     if (a.T <= 0) return hipSuccess;
-    rope_kv_write_kernel<<<a.T, 256, 0, stream>>>(a);
+    switch (a.planes) {
+        case 1: rope_kv_write_kernel<1><<<a.T, 256, 0, stream>>>(a); break;
+        case 2: rope_kv_write_kernel<2><<<a.T, 256, 0, stream>>>(a); break;
+        case 4: rope_kv_write_kernel<4><<<a.T, 256, 0, stream>>>(a); break;
+        case 8: rope_kv_write_kernel<8><<<a.T, 256, 0, stream>>>(a); break;
+        default: rope_kv_write_kernel<-1><<<a.T, 256, 0, stream>>>(a); break;
+    }
     return hipGetLastError();
 }
