@@ -59,7 +59,7 @@ gllm_status gllm_sched_add_request(gllm_sched* s, int64_t request_id, int32_t pr
  * skips the whole pages found (cached_len of its first chunk is then 16 x pages found; at least one token is always
  * left to compute); whole pages of this prompt are registered when the chunk that fills them has left the last
  * stage, until one registration fails; registered pages nobody holds count as free pages in Eq. 3.  Generated tokens
- * are never registered.  Shared pages are only read: a chunk's new tokens always start on a page of its own.  With
+ * are registered only when reported (gllm_sched_complete_batch_tokens).  Shared pages are only read: a chunk's new tokens always start on a page of its own.  With
  * prefix_caching = 0, or a null prompt_tokens, this is gllm_sched_add_request(). */
 gllm_status gllm_sched_add_request_tokens(gllm_sched* s, int64_t request_id, const int32_t* prompt_tokens, int32_t prompt_len,
                                           int32_t output_len);
@@ -82,6 +82,15 @@ gllm_status gllm_sched_batch_block_tables(const gllm_sched* s, int64_t batch_id,
  * reached output_len end and return their pages.  finished_ids (room for `capacity`) receives their ids. */
 gllm_status gllm_sched_complete_batch(gllm_sched* s, int64_t batch_id, int64_t* finished_ids, int32_t capacity,
                                       int32_t* num_finished);
+
+/* The same, reporting the tokens the micro-batch produced: row_tokens[i] is the token row i yielded (decode rows and
+ * the chunk that completes a prompt yield one; the entry is ignored for other rows; negative = not reported), num_rows
+ * must equal the micro-batch's row count.  With prefix caching a request's reported tokens extend its known tokens, so
+ * pages filled during decoding are registered as well (a page is registered when the step that computes its last
+ * position has completed): a follow-up request that repeats the conversation so far, and the request itself after a
+ * preemption, find them.  A request whose tokens were not reported without gaps simply stops extending. */
+gllm_status gllm_sched_complete_batch_tokens(gllm_sched* s, int64_t batch_id, const int32_t* row_tokens, int32_t num_rows,
+                                             int64_t* finished_ids, int32_t capacity, int32_t* num_finished);
 
 typedef struct gllm_sched_state {
     int64_t tokens_waiting;   /* #WP */

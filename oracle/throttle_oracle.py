@@ -38,9 +38,12 @@ Readings where the paper is silent or at odds with itself (each is a parameter-f
   R9  with prefix caching (section 3.4 lists it among the integrated techniques; off in the paper's runs,
       section 4.1) a request that is about to receive its first chunk, or starts over after a preemption, first
       looks its prompt up in the pool and skips the whole pages found, leaving at least one token to compute;
-      whole pages of the prompt as given on arrival are registered when the chunk that fills them has left the
-      last stage, until one registration fails; pages nobody holds that still carry a registered prefix count
-      as idle KV memory in Eq. 2 / Eq. 3 (they are reclaimed on demand).  Generated tokens are never registered.
+      whole pages of known tokens are registered when the micro-batch that fills them has left the last stage,
+      until one registration fails; pages nobody holds that still carry a registered prefix count as idle KV
+      memory in Eq. 2 / Eq. 3 (they are reclaimed on demand).  Known tokens are the prompt as given on arrival
+      and the generated tokens the caller reports with complete_batch() (a follow-up request that repeats the
+      conversation so far then finds the answer's pages too); the newest token is known one step before its KV
+      is in the cache, so a page is registered when the step that computes its last position has completed.
 """
 from collections import deque
 from dataclasses import dataclass
@@ -104,7 +107,7 @@ class Request:
     chunk: int = 0          # tokens of the chunk in flight
     admitted: int = -1      # order of entering the decode phase (for R6)
     block_table: list = None
-    tokens: Optional[list] = None   # the prompt as given on arrival (R9)
+    tokens: Optional[list] = None   # known token ids from position 0 on: the prompt, then reported output tokens (R9)
     registered: int = 0             # leading pages of the block table that are in the pool's tree
     registering: bool = True
 
@@ -148,9 +151,10 @@ class Scheduler:
         r.prefilled = len(found) * PAGE
         self.hit_tokens += r.prefilled
 
-    def _register(self, r: Request) -> None:
-        """R9: the pages a completed chunk has filled with tokens of the original prompt enter the tree."""
-        full = min(r.prefilled, len(r.tokens)) // PAGE
+    def _register(self, r: Request, in_cache: int) -> None:
+        """R9: whole pages among the first in_cache positions (those whose KV has been computed) whose tokens are
+        known enter the tree."""
+        full = min(in_cache, len(r.tokens)) // PAGE
         while r.registering and r.registered < full:
             i = r.registered
             parent = r.block_table[i - 1] if i > 0 else ROOT
@@ -266,10 +270,11 @@ class Scheduler:
         self.waiting.appendleft(rid)
         self.preemptions += 1
 
-    def complete_batch(self, bid: int) -> List[int]:
-        """The micro-batch has left the last stage.  Returns the ids of the requests that ended."""
+    def complete_batch(self, bid: int, new_tokens: Optional[Sequence[int]] = None) -> List[int]:
+        """The micro-batch has left the last stage.  new_tokens: per row the token it produced (ignored for rows
+        that produce none; negative = not reported).  Returns the ids of the requests that ended."""
         done = []
-        for rid, n, c, is_decode in self.in_flight.pop(bid):
+        for i, (rid, n, c, is_decode) in enumerate(self.in_flight.pop(bid)):
             r = self.req[rid]
             r.in_flight = False
             if is_decode:
@@ -277,15 +282,20 @@ class Scheduler:
             else:
                 r.chunk = 0
                 r.prefilled += n
-                if r.tokens is not None:
-                    self._register(r)
                 if r.prefilled < r.prompt_len:
+                    if r.tokens is not None:
+                        self._register(r, r.prefilled)
                     continue
                 self.waiting.remove(rid)
                 r.generated = 1                      # the last chunk yields the first output token
                 r.admitted = self.admit_counter
                 self.admit_counter += 1
                 self.n_decode += 1
+            if r.tokens is not None:
+                in_cache = r.prompt_len + r.generated - 1        # the newest token's KV is not computed yet
+                if new_tokens is not None and new_tokens[i] >= 0 and len(r.tokens) == in_cache:
+                    r.tokens.append(int(new_tokens[i]))
+                self._register(r, in_cache)
             if r.generated >= r.output_len:
                 self.n_decode -= 1
                 self._release(r)

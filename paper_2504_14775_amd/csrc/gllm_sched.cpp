@@ -47,8 +47,9 @@ struct Seq {
     int64_t decode_rank = -1;  // order of entering the decode phase
     bool flying = false;
     std::vector<int32_t> pages;
-    // prefix caching: the prompt as given on arrival, how many leading pages of `pages` are in the pool's tree,
-    // and whether this request still registers the pages it fills
+    // prefix caching: the token ids known from position 0 on (the prompt as given on arrival, then the output
+    // tokens the caller has reported), how many leading pages of `pages` are in the pool's tree, and whether this
+    // request still registers the pages it fills
     std::vector<int32_t> tokens;
     int64_t entered = 0;
     bool entering = true;
@@ -100,10 +101,10 @@ struct gllm_sched {
         waiting_tokens -= s.prefilled;
         hit_tokens += s.prefilled;
     }
-    // The whole pages a finished chunk has filled with tokens of the original prompt enter the pool's tree, until a
-    // page turns out to be there already.
-    void enter_filled_pages(Seq& s) {
-        const int64_t whole = std::min<int64_t>(s.prefilled, (int64_t)s.tokens.size()) / kPageTokens;
+    // The whole pages of known tokens among the first in_cache positions (those whose KV has been computed) enter
+    // the pool's tree, until a page turns out to be there already.
+    void enter_filled_pages(Seq& s, int64_t in_cache) {
+        const int64_t whole = std::min<int64_t>(in_cache, (int64_t)s.tokens.size()) / kPageTokens;
         while (s.entering && s.entered < whole) {
             const size_t i = (size_t)s.entered;
             const int32_t parent = i ? s.pages[i - 1] : gllm::PagePool::kRoot;
@@ -194,13 +195,15 @@ struct gllm_sched {
         flying.emplace(id, std::move(rows));
         return id;
     }
-    // Returns the ids of the requests that ended, in row order.
-    std::vector<int64_t> retire(int64_t batch) {
+    // Returns the ids of the requests that ended, in row order.  row_tokens: per row the token it produced (null or
+    // negative: not reported).
+    std::vector<int64_t> retire(int64_t batch, const int32_t* row_tokens = nullptr) {
         std::vector<int64_t> ended;
         auto it = flying.find(batch);
         std::vector<Row> rows = std::move(it->second);
         flying.erase(it);
-        for (const Row& r : rows) {
+        for (size_t i = 0; i < rows.size(); ++i) {
+            const Row& r = rows[i];
             Seq& s = seqs[r.id];
             s.flying = false;
             if (r.decode) {
@@ -208,12 +211,19 @@ struct gllm_sched {
             } else {
                 s.chunk = 0;
                 s.prefilled += r.count;
-                if (!s.tokens.empty()) enter_filled_pages(s);
-                if (s.prefilled < s.prompt) continue;
+                if (s.prefilled < s.prompt) {
+                    if (!s.tokens.empty()) enter_filled_pages(s, s.prefilled);
+                    continue;
+                }
                 waiting.erase(std::find(waiting.begin(), waiting.end(), r.id));
                 s.produced = 1;
                 s.decode_rank = next_rank++;
                 ++decode_total;
+            }
+            if (!s.tokens.empty()) {
+                const int64_t in_cache = s.prompt + s.produced - 1;  // the newest token's KV is not computed yet
+                if (row_tokens && row_tokens[i] >= 0 && (int64_t)s.tokens.size() == in_cache) s.tokens.push_back(row_tokens[i]);
+                enter_filled_pages(s, in_cache);
             }
             if (s.produced >= s.output) {
                 --decode_total;
@@ -301,11 +311,17 @@ gllm_status gllm_sched_batch_block_tables(const gllm_sched* s, int64_t batch_id,
 
 gllm_status gllm_sched_complete_batch(gllm_sched* s, int64_t batch_id, int64_t* finished_ids, int32_t capacity,
                                       int32_t* num_finished) {
+    return gllm_sched_complete_batch_tokens(s, batch_id, nullptr, 0, finished_ids, capacity, num_finished);
+}
+
+gllm_status gllm_sched_complete_batch_tokens(gllm_sched* s, int64_t batch_id, const int32_t* row_tokens, int32_t num_rows,
+                                             int64_t* finished_ids, int32_t capacity, int32_t* num_finished) {
     if (!s || !num_finished || capacity < 0 || (capacity > 0 && !finished_ids)) return GLLM_E_INVALID;
     auto it = s->flying.find(batch_id);
     if (it == s->flying.end()) return GLLM_E_INVALID;
+    if (row_tokens && (size_t)num_rows != it->second.size()) return GLLM_E_INVALID;
     if ((size_t)capacity < it->second.size()) return GLLM_E_CAPACITY;
-    const std::vector<int64_t> ended = s->retire(batch_id);
+    const std::vector<int64_t> ended = s->retire(batch_id, row_tokens);
     std::copy(ended.begin(), ended.end(), finished_ids);
     *num_finished = (int32_t)ended.size();
     return GLLM_OK;

@@ -189,7 +189,9 @@ class Engine:
             news.append(rid)
         if self.observer is not None:
             self.observer(slot)
-        ended = set(self.sched.complete_batch(slot.batch_id))
+        row_tokens = np.full(len(slot.rows), -1, dtype=np.int32)      # reported, so that answers enter the prefix cache
+        row_tokens[slot.takers] = picked[:len(slot.takers)]
+        ended = set(self.sched.complete_batch(slot.batch_id, row_tokens))
         for rid in ended:
             self.requests[rid].done = True
         self.stats["tokens_generated"] += len(news)

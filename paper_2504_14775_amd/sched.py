@@ -12,7 +12,7 @@ from .binding import GLLM_OK, GllmError, load_library
 EXPORTS = [
     "gllm_sched_prefill_budget", "gllm_sched_decode_budget", "gllm_sched_create", "gllm_sched_destroy",
     "gllm_sched_add_request", "gllm_sched_add_request_tokens", "gllm_sched_next_batch", "gllm_sched_batch_block_tables",
-    "gllm_sched_complete_batch", "gllm_sched_get_state", "gllm_sched_simulate", "gllm_sched_simulate_tokens",
+    "gllm_sched_complete_batch", "gllm_sched_complete_batch_tokens", "gllm_sched_get_state", "gllm_sched_simulate", "gllm_sched_simulate_tokens",
 ]
 
 CHUNKED_PREFILL, TOKEN_THROTTLING = 0, 1
@@ -88,6 +88,8 @@ def _lib():
         lib.gllm_sched_batch_block_tables.argtypes = [vp, i64, P(i32), i32]
         lib.gllm_sched_complete_batch.restype = i32
         lib.gllm_sched_complete_batch.argtypes = [vp, i64, P(i64), i32, P(i32)]
+        lib.gllm_sched_complete_batch_tokens.restype = i32
+        lib.gllm_sched_complete_batch_tokens.argtypes = [vp, i64, P(i32), i32, P(i64), i32, P(i32)]
         lib.gllm_sched_get_state.restype = i32
         lib.gllm_sched_get_state.argtypes = [vp, P(gllm_sched_state)]
         lib.gllm_sched_simulate.restype = i32
@@ -164,12 +166,19 @@ class Scheduler:
                     "gllm_sched_batch_block_tables")
         return bt
 
-    def complete_batch(self, batch_id: int, capacity: Optional[int] = None) -> List[int]:
+    def complete_batch(self, batch_id: int, row_tokens=None, capacity: Optional[int] = None) -> List[int]:
+        """row_tokens: per row of the micro-batch the token it produced (negative: none / not reported)."""
         cap = self._count if capacity is None else capacity
         out = np.empty(max(cap, 1), dtype=np.int64)
         n = C.c_int32(0)
-        self._check(self.lib.gllm_sched_complete_batch(self.handle, batch_id, _ptr(out, C.c_int64), cap, C.byref(n)),
-                    "gllm_sched_complete_batch")
+        if row_tokens is None:
+            self._check(self.lib.gllm_sched_complete_batch(self.handle, batch_id, _ptr(out, C.c_int64), cap, C.byref(n)),
+                        "gllm_sched_complete_batch")
+        else:
+            t = np.ascontiguousarray(row_tokens, dtype=np.int32)
+            self._check(self.lib.gllm_sched_complete_batch_tokens(self.handle, batch_id, _ptr(t, C.c_int32), len(t),
+                                                                  _ptr(out, C.c_int64), cap, C.byref(n)),
+                        "gllm_sched_complete_batch_tokens")
         return [int(x) for x in out[:n.value]]
 
     def state(self) -> dict:

@@ -89,6 +89,15 @@ def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sample
     for r in late:
         eng.add_request(r, prompts[r], out_len[r])
         result = eng.run()
+    if caching:
+        # a follow-up that repeats a finished conversation: the pages of the answer are found as well
+        before = eng.sched.state()["prefix_hit_tokens"]
+        talk = prompts[1] + result[1]                       # 70 prompt tokens + 9 answer tokens
+        prompts.append(talk + rng.integers(0, V, size=12).tolist())
+        out_len.append(3)
+        eng.add_request(6, prompts[6], out_len[6])
+        result = eng.run()
+        assert len(talk) == 79 and eng.sched.state()["prefix_hit_tokens"] - before == 64   # 4 whole pages of the 78 cached positions
     st = eng.sched.state()
     assert {r: len(t) for r, t in result.items()} == dict(enumerate(out_len))
     assert st["free_pages"] == pages and st["batches_in_flight"] == 0

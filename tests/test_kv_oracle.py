@@ -259,8 +259,9 @@ def test_without_shared_content_caching_changes_no_row_of_the_schedule():
     assert logs[0] == logs[1]
 
 
+@pytest.mark.parametrize("report", [False, True])
 @pytest.mark.parametrize("seed,pages,policy", [(0, 40, T.THROTTLE), (1, 24, T.THROTTLE), (2, 30, T.SARATHI), (3, 200, T.THROTTLE)])
-def test_every_cached_position_a_row_relies_on_holds_the_kv_of_that_requests_own_prefix(seed, pages, policy):
+def test_every_cached_position_a_row_relies_on_holds_the_kv_of_that_requests_own_prefix(seed, pages, policy, report):
     """The property prefix caching must keep: row (request, n, c) reads positions 0..c-1 through its block table,
     and each must have been written for exactly this request's tokens 0..position.  The shadow KV store is keyed by
     (page, slot) and written at launch, in launch order (a pipeline runs micro-batches in order)."""
@@ -294,9 +295,11 @@ def test_every_cached_position_a_row_relies_on_holds_the_kv_of_that_requests_own
                 for pos in range(c, c + n):
                     store[(bt[pos // PAGE], pos % PAGE)] = tuple(full[rid][:pos + 1])
                 computed += n
-            flying.append(bid)
+            flying.append((bid, rows))
         if flying and (got is None or len(flying) == 3):
-            s.complete_batch(flying.pop(0))
+            bid, rows = flying.pop(0)
+            # every row reports the token that follows its last position (rows that yield none ignore it)
+            s.complete_batch(bid, [full[rid][c + n] if report and c + n < len(full[rid]) else -1 for rid, n, c in rows])
         live = [r for r in full if full[r] is not None]
         if nxt == n_req and len(s.finished) == len(live) and not flying:
             break
@@ -305,3 +308,50 @@ def test_every_cached_position_a_row_relies_on_holds_the_kv_of_that_requests_own
     assert s.hit_tokens > 0                     # the stems do get shared
     if pages <= 40:
         assert s.preemptions > 0                # and the small pools force recomputation on top
+
+
+def test_a_follow_up_request_finds_the_pages_of_the_reported_answer():
+    s = T.Scheduler(params(pp_depth=1))
+    prompt = list(range(500, 540))                                   # 40 tokens
+    answer = list(range(900, 930))                                   # 30 tokens
+    s.add_request(0, 40, 30, prompt)
+    step = 0
+    while True:
+        got = s.next_batch()
+        if got is None:
+            break
+        bid, rows = got
+        s.complete_batch(bid, [answer[step]])                        # one row per micro-batch here
+        step += 1
+    assert step == 30 and s.finished == [0]
+    # the cache holds positions 0..68 (the last answer token was never fed back): 4 whole pages of known tokens
+    follow_up = prompt + answer + list(range(100, 120))              # 90 tokens
+    s.add_request(1, 90, 1, follow_up)
+    assert s.next_batch()[1] == [(1, 26, 64)]
+    # the same conversation when the answer was not reported: only the prompt's two whole pages are found
+    s2 = T.Scheduler(params(pp_depth=1))
+    s2.add_request(0, 40, 30, prompt)
+    run_to_end(s2)
+    s2.add_request(1, 90, 1, follow_up)
+    assert s2.next_batch()[1] == [(1, 58, 32)]
+
+
+def test_a_recomputed_request_finds_its_own_answer_so_far():
+    """6 pages cannot hold both requests to their ends: one is preempted while decoding, and when it starts over
+    its first chunk begins behind more whole pages than its prompt has -- pages that hold answer tokens and can
+    only be in the tree because reported tokens are registered."""
+    s = T.Scheduler(params(pp_depth=1, total_pages=6, min_p=1))
+    s.add_request(0, 40, 40, list(range(1000, 1040)))               # grows to 5 pages
+    s.add_request(1, 10, 30, list(range(2000, 2010)))               # grows to 3 pages
+    restarts = []
+    for _ in range(400):
+        got = s.next_batch()
+        if got is None:
+            break
+        bid, rows = got
+        restarts += [(rid, n, c) for rid, n, c in rows if n > 1 and c > 0]     # prompts go in one chunk here unless cached
+        s.complete_batch(bid, [7000 + 100 * rid + c + n for rid, n, c in rows])  # a token that depends on its position
+    assert sorted(s.finished) == [0, 1] and s.preemptions > 0
+    whole_prompt_pages = {0: 32, 1: 0}                              # what the prompts alone could give
+    assert restarts and all(c % 16 == 0 and c > whole_prompt_pages[rid] for rid, n, c in restarts)
+    assert s.free_pages == 6

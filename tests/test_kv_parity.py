@@ -129,17 +129,25 @@ def shared_prompt(rng, stems, max_tail):
     return stem[:rng.randrange(0, len(stem) + 1)] + [rng.randrange(10, 30000) for _ in range(rng.randrange(1, max_tail))]
 
 
+@pytest.mark.parametrize("report", [False, True])
 @pytest.mark.parametrize("policy", [T.SARATHI, T.THROTTLE])
 @pytest.mark.parametrize("pages,thresh,seed", [(4000, 500, 1), (260, 500, 2), (260, 0, 3), (120, 1000, 4)])
-def test_step_by_step_agreement_with_shared_prefixes(policy, pages, thresh, seed):
+def test_step_by_step_agreement_with_shared_prefixes(policy, pages, thresh, seed, report):
     po, pn = both(policy=policy, total_pages=pages, kv_thresh_bp=thresh)
     so, sn = T.Scheduler(po), S.Scheduler(pn)
     rng = random.Random(seed)
     stems = [[rng.randrange(10) for _ in range(rng.randrange(100, 600))] for _ in range(5)]
     flying, next_id, n_req = [], 0, 90
+    rows_of = {}
+    history = []                                     # finished conversations: a later request may continue one
+    text = {}
     for step in range(20000):
         if next_id < n_req and rng.random() < 0.3:
             prompt, ol = shared_prompt(rng, stems, 200), rng.randrange(1, 100)
+            if report and history and rng.random() < 0.3:
+                prompt = rng.choice(history) + [rng.randrange(10, 30000) for _ in range(rng.randrange(1, 60))]
+                prompt = prompt[:700]
+            text[next_id] = list(prompt)
             if rng.random() < 0.15:
                 so.add_request(next_id, len(prompt), ol)                 # some requests come without content
                 sn.add_request(next_id, len(prompt), ol)
@@ -149,12 +157,22 @@ def test_step_by_step_agreement_with_shared_prefixes(policy, pages, thresh, seed
             next_id += 1
         if flying and (len(flying) >= po.pp_depth or rng.random() < 0.4):
             bid = flying.pop(rng.randrange(len(flying)) if rng.random() < 0.2 else 0)
-            assert sn.complete_batch(bid) == so.complete_batch(bid)
+            toks = None
+            if report:                               # a made-up token per row; some are withheld
+                toks = [(-1 if rng.random() < 0.02 else (r * 7919 + c + n) % 30000) for r, n, c in rows_of[bid]]
+                for (r, n, c), t in zip(rows_of[bid], toks):
+                    q = so.req[r]
+                    if q.tokens is not None and t >= 0 and c + n == len(text[r]) and c + n >= q.prompt_len:
+                        text[r].append(t)            # the conversation as a client would see it
+            ended = so.complete_batch(bid, toks)
+            assert sn.complete_batch(bid, toks) == ended
+            history += [text[r] for r in ended if so.req[r].tokens is not None]
         go, gn = so.next_batch(), sn.next_batch()
         assert go == gn, step
         if go is not None:
             bid, rows = go
             flying.append(bid)
+            rows_of[bid] = rows
             stride = max(len(so.req[r].block_table) for r, _, _ in rows) + 1
             want = np.full((len(rows), stride), -1, dtype=np.int32)
             for i, (r, _, _) in enumerate(rows):
