@@ -67,11 +67,14 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const bf16_t* __restrict_
 
 // ---- sampling: one workgroup per row ----------------------------------------------------------------------
 // The row of logits (0.5 MB at a 128k vocabulary) does not fit on chip, so the cost is the number of passes over
-// it: 1 (maximum) + 4 (radix select of the k-th largest, only with top-k) + then either
-//   * at most kCompact tokens survive top-k (the usual top_k = 20..100): they are gathered into LDS once and
-//     nucleus and draw work on that short list, or
+// it.  With top-k: pass 1 takes the maximum and counts the top byte of the logits' keys, pass 2 counts the second
+// byte inside the bin of the k-th largest, pass 3 gathers the tokens at or above that 16-bit prefix into a list
+// in LDS, on which the k-th largest is selected (rows whose candidates do not fit the list fall back to one pass
+// per key byte).  Then either
+//   * at most kCompact tokens survive top-k (the usual top_k = 20..100): nucleus and draw work on that short
+//     list, or
 //   * the nucleus threshold is searched over the whole row, 15 candidate thresholds per pass (8 passes), and the
-//     draw takes one more pass.
+//     draw takes one more.
 constexpr int kSampleThreads = 1024;
 constexpr int kSampleWaves = kSampleThreads / 64;
 constexpr int kCompact = 1024;
