@@ -10,6 +10,8 @@ tables, token-id upload, the kernels, the read-back of the sampled ids) with up 
 `synchronous` repeats the run with one micro-batch in flight, i.e. with the host work exposed; `gpu_busy` is the share
 of the wall time covered by the micro-batches' own event-timed durations.  All requests are present at the start;
 prompt and output lengths are log-normal (medians 220 and 64), a stand-in for a chat workload.
+`serving` replays the same requests with Poisson arrivals at --rate requests per second (wall clock) and reports the
+latency metrics of the paper's section 4.1: time to first token, time per output token, end-to-end latency.
 """
 import argparse
 import json
@@ -28,6 +30,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--requests", type=int, default=1024)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--rate", type=float, default=100.0, help="arrivals per second of the serving run (0: skip it)")
     args = ap.parse_args()
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -65,6 +68,43 @@ def main():
                 "micro_batches": st["micro_batches"], "mean_tokens_per_micro_batch": round(st["tokens_computed"] / st["micro_batches"], 1),
                 "ms_per_micro_batch": round(wall * 1e3 / st["micro_batches"], 3), "gpu_busy": round(st["gpu_ms"] * 1e-3 / wall, 4)}
 
+    def serve(rate):
+        """Poisson arrivals on the wall clock; a request is admitted when its time has come."""
+        eng = E.Engine(shape, V, params, max_batch_tokens=2048 + args.requests, max_batch_seqs=args.requests + 8,
+                       max_context=2048 + 256, device=dev)
+        eng.load(layers, table, gain, w_vocab)
+        arr, t = [], 0.0
+        for _ in reqs:
+            t += rng.expovariate(rate)
+            arr.append(t)
+        first, last, nxt, done = {}, {}, 0, 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while done < len(reqs):
+            now = time.perf_counter() - t0
+            while nxt < len(reqs) and arr[nxt] <= now:
+                eng.add_request(nxt, reqs[nxt][0], reqs[nxt][1], E.Sampling(temperature=0.8, top_k=50, top_p=0.95, seed=nxt))
+                nxt += 1
+            news = eng.step()
+            now = time.perf_counter() - t0
+            for rid, _, ended in news:
+                first.setdefault(rid, now)
+                if ended:
+                    last[rid] = now
+                    done += 1
+            if not news and not eng.flying and nxt < len(reqs):
+                time.sleep(max(0.0, min(arr[nxt] - (time.perf_counter() - t0), 0.002)))
+        wall = time.perf_counter() - t0
+        eng.close()
+        ttft = sorted(first[i] - arr[i] for i in range(len(reqs)))
+        e2e = sorted(last[i] - arr[i] for i in range(len(reqs)))
+        tpot = sorted((last[i] - first[i]) / (reqs[i][1] - 1) for i in range(len(reqs)) if reqs[i][1] > 1)
+        pct = lambda v, q: round(1e3 * v[min(len(v) - 1, int(q * len(v)))], 2)
+        return {"arrival_rate_per_s": rate, "wall_s": round(wall, 2), "generated_tokens_per_s": round(sum(o for _, o in reqs) / wall, 1),
+                "ttft_ms": {"mean": round(1e3 * sum(ttft) / len(ttft), 2), "p50": pct(ttft, 0.5), "p99": pct(ttft, 0.99)},
+                "tpot_ms": {"mean": round(1e3 * sum(tpot) / len(tpot), 2), "p50": pct(tpot, 0.5), "p99": pct(tpot, 0.99)},
+                "e2e_ms": {"mean": round(1e3 * sum(e2e) / len(e2e), 2), "p50": pct(e2e, 0.5), "p99": pct(e2e, 0.99)}}
+
     run(None)                                               # warm-up: first-use costs of every kernel
     ahead = run(None)
     sync = run(1)
@@ -75,7 +115,7 @@ def main():
         "config": {"workload": f"{args.requests} requests at once, 8 layers of the Llama-3-8B shape as the whole model, vocabulary {V}",
                    "prompt_tokens": sum(len(p) for p, _ in reqs), "output_tokens": sum(o for _, o in reqs),
                    "scheduler": "token throttling T=8 MaxP=2048 MinP=32 KV_thresh=0.05 depth=4", "sampling": "temperature 0.8, top-k 50, top-p 0.95"},
-        "enqueued_ahead": ahead, "synchronous": sync}))
+        "enqueued_ahead": ahead, "synchronous": sync, "serving": serve(args.rate) if args.rate > 0 else None}))
 
 
 if __name__ == "__main__":
