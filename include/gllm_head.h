@@ -49,8 +49,8 @@ gllm_status gllm_head_bind_workspace(gllm_head* head, void* workspace /*DEVICE*/
  * the head's own padded buffers (DEVICE inputs; the caller may free them once `stream` has passed this point). */
 gllm_status gllm_head_load(gllm_head* head, const void* norm_gain, const void* w_vocab, void* stream);
 
-/* Logits of selected rows (section 2.1: "a linear projection layer transforms the final hidden states into
- * logits"): logits[i][v] = sum_j h[j] * w_vocab[v][j] with h = bf16(x[rows[i]] * rsqrt(mean_j x^2 + eps) * gain),
+/* Logits of selected rows (section 2.1: after the last layer a linear projection turns the final hidden states
+ * into logits): logits[i][v] = sum_j h[j] * w_vocab[v][j] with h = bf16(x[rows[i]] * rsqrt(mean_j x^2 + eps) * gain),
  * fp32 accumulation on the matrix cores.
  *   x        DEVICE float [num_x_rows][hidden]: the fp32 residual stream the last stage returns
  *            (gllm_stage_forward's hidden_out_f32)
