@@ -142,6 +142,8 @@ gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);
  *   "overlap_attention" (default 1): prefill attention of a layer runs on an internal side stream next to
  *   decode attention (forked from and joined back into the caller's stream with events); 0 keeps every
  *   kernel on the caller's stream.  Per-kernel profiling always uses the single-stream order.
+ *   "gemm_row_mixed" (default 1; process-wide, not per stage): the GEMM planner may cover a last band of at most
+ *   128 token rows with 64- or 128-row tiles instead of a whole band of 256 (tile 8 of gllm_op_gemm_bf16).
  * Unknown names give GLLM_E_INVALID. */
 gllm_status gllm_stage_set_option(gllm_stage* stage, const char* name /*HOST*/, int64_t value);
 
@@ -176,7 +178,9 @@ const char* gllm_profile_class_name(int32_t i);
  * 256x128 tiles for the remainder (only for shapes with such a remainder), 5 = 256x192 (n a multiple of 192,
  * not for SwiGLU), 6 = 128x128 with four LDS stages instead of two (for few rows, where the weights stream
  * from HBM), 7 = 64x128 with three LDS stages (picked up to 64 rows: two workgroups per compute unit keep more
- * of the weight stream in flight); a forced tile that does not fit the shape gives GLLM_E_UNSUPPORTED. */
+ * of the weight stream in flight), 8 = 256x256 tiles for the whole bands of 256 rows plus 64x256 or 128x256 tiles
+ * for a last band of at most 128 rows (only for m > 256 with 0 < m mod 256 <= 128 and n a multiple of 256); a forced
+ * tile that does not fit the shape gives GLLM_E_UNSUPPORTED. */
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
                               int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream);
 

@@ -34,13 +34,17 @@ enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 // out (op)= a[m x k] * w[n x k]^T, see gllm_op_gemm_bf16 in the public header.
 // tile: -1 picks a tile shape from m and n; 0..3 force one (128x128, 256x128, 256x256, 256x256 with 8 waves);
 // 4 forces the mixed 256x256 + 256x128 launch (only where gemm_mixed_rem_cols(m, n) > 0); 5 = 256x192 (not SwiGLU);
-// 6 = 128x128 with four LDS stages; 7 = 64x128 with three LDS stages (up to 64 rows per tile row: weight streaming).
+// 6 = 128x128 with four LDS stages; 7 = 64x128 with three LDS stages (up to 64 rows per tile row: weight streaming);
+// 8 = 256x256 tiles for the whole bands of 256 rows plus 64x256 or 128x256 tiles for a last band of at most 128 rows
+// (only where gemm_rowmix_rem_rows(m, n) > 0).
 // splits > 1 (store mode only): split s covers k range [s*k/splits, (s+1)*k/splits) and writes its partial
 // product to out + s*split_stride floats; the consumer sums the planes in order.
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,
                             int m, int n, int k, int mode, int tile, int splits, int64_t split_stride,
                             hipStream_t stream);
 int gemm_mixed_rem_cols(int m, int n);
+int gemm_rowmix_rem_rows(int m, int n);
+void gemm_plan_row_mixed(bool on);  // whether gemm_plan() may pick tile 8 (process-wide; on by default)
 // Tile id and split-K factor the cost model prefers (splits stays 1 unless mode is GEMM_STORE_F32).
 struct GemmPlan { int tile; int splits; };
 GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits);

@@ -374,6 +374,10 @@ gllm_status gllm_stage_set_option(gllm_stage* s, const char* name, int64_t value
         s->overlap_attention = value != 0;
         return GLLM_OK;
     }
+    if (std::strcmp(name, "gemm_row_mixed") == 0) {  // process-wide: the planner is shared by all stages
+        gemm_plan_row_mixed(value != 0);
+        return GLLM_OK;
+    }
     if (std::strcmp(name, "decode_min_workgroups") == 0) {
         if (value < 1) return fail(s, GLLM_E_INVALID, "decode_min_workgroups must be positive");
         s->decode_min_workgroups = value;

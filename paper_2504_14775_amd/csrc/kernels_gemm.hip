@@ -37,13 +37,13 @@ typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 // The work of one workgroup: output tile number `wg_linear` of a tiles_m x tiles_n grid of BM x BN tiles
-// whose first column is n_base.
+// whose first column is n_base and whose first row is m_base.
 // NS LDS stages of 64 k-values each (NS = 2 fills LDS for the 256x256 tile).
 template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
                                           int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
                                           int tiles_m, int tiles_n, int n_base, int wg_linear,
-                                          int64_t split_stride) {
+                                          int64_t split_stride, int m_base = 0) {
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
@@ -69,7 +69,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     const int in_band = wg - band * BAND * tiles_m;
     const int tile_m = in_band / band_cols;
     const int tile_n = band * BAND + in_band % band_cols;
-    const int m0 = tile_m * BM, n0 = n_base + tile_n * BN;
+    const int m0 = m_base + tile_m * BM, n0 = n_base + tile_n * BN;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -289,6 +289,22 @@ __global__ __launch_bounds__(512) void gemm_bf16_mixed_kernel(const bf16_t* __re
                                         blockIdx.x - big_tiles, 0);
 }
 
+// Two tile heights in one launch: the first big_tiles workgroups cover the whole bands of 256 rows with 256x256
+// tiles, the rest cover the last band -- at most BMR rows are left -- with BMR x 256 tiles, so a row count just above a
+// multiple of 256 does not pay for a whole band of padding.  8 waves either way; blockIdx.y is the split-K share.
+template <int MODE, int BMR>
+__global__ __launch_bounds__(512) void gemm_bf16_rowmix_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                const bf16_t* __restrict__ W, int64_t ldw,
+                                                                void* __restrict__ out, int64_t ldc, int M, int K,
+                                                                int bands, int tiles_n, int64_t split_stride) {
+    const int big_tiles = bands * tiles_n;
+    if ((int)blockIdx.x < big_tiles)
+        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, bands, tiles_n, 0, blockIdx.x, split_stride);
+    else
+        gemm_tile<BMR, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, 1, tiles_n, 0, blockIdx.x - big_tiles, split_stride,
+                                        bands * 256);
+}
+
 template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                        int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
@@ -347,7 +363,43 @@ hipError_t launch_mixed(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t l
     return hipGetLastError();
 }
 
+// Row-mixed launch (see gemm_bf16_rowmix_kernel); rem_rows is 64 or 128.
+template <int MODE>
+hipError_t launch_rowmix(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
+                         int n, int k, int rem_rows, int splits, int64_t split_stride, hipStream_t stream) {
+    const int bands = m / 256, tiles_n = n / 256;
+    const size_t smem = 2 * (256 + 256) * BK * sizeof(bf16_t);
+    const dim3 grid((bands + 1) * tiles_n, splits);
+#define GLLM_ROWMIX(R)                                                                                             \
+    do {                                                                                                           \
+        auto kern = gemm_bf16_rowmix_kernel<MODE, R>;                                                              \
+        static bool configured = false;                                                                            \
+        if (!configured) {                                                                                         \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);             \
+            if (e != hipSuccess) return e;                                                                         \
+            configured = true;                                                                                     \
+        }                                                                                                          \
+        kern<<<grid, 512, smem, stream>>>(a, lda, w, ldw, out, ldc, m, k, bands, tiles_n, split_stride);          \
+    } while (0)
+    if (rem_rows == 64) GLLM_ROWMIX(64);
+    else GLLM_ROWMIX(128);
+#undef GLLM_ROWMIX
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// Height of the last row band for a row-mixed launch (64 or 128), or 0 when the shape does not call for one: at
+// least one whole band of 256 rows and at most 128 rows left over.
+static bool g_rowmix_planned = true;
+void gemm_plan_row_mixed(bool on) { g_rowmix_planned = on; }
+
+int gemm_rowmix_rem_rows(int m, int n) {
+    if (n % 256 != 0 || m <= 256) return 0;
+    const int r = m % 256;
+    return r == 0 || r > 128 ? 0 : r <= 64 ? 64 : 128;
+}
 
 // Number of 256-wide tile columns to split in two for a mixed launch, or 0 when a plain launch is as good:
 // worth it when the last round of 256x256 tiles would occupy at most half of the compute units.
@@ -381,6 +433,20 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
         const double steps = (double)its / s;
         const double plane_cost = (double)m * n * 4.0 * s / 8e12 / 1.65e-6;  // mostly hidden under other tiles
         const bool skinny = m <= 64 && n % 128 == 0;
+        if (g_rowmix_planned && gemm_rowmix_rem_rows(m, n) > 0) {
+            // (evaluated first: on equal cost it is kept -- whole rounds hide that it always does less work)
+            // whole bands as 256x256 tiles; the last band's tiles cost 0.4 (64 rows) or 0.6 (128 rows) of one and go
+            // first into the compute units the last round of big tiles leaves idle
+            const int rr = gemm_rowmix_rem_rows(m, n);
+            const double frac = rr == 64 ? 0.4 : 0.6;
+            const int64_t big = (int64_t)(m / 256) * (n / 256) * s, small = (int64_t)(n / 256) * s;
+            const int64_t rem_big = big % 256;
+            const int64_t room = rem_big > 0 ? (256 - rem_big) * (rr == 64 ? 2 : 1) : 0;
+            double rounds = (double)ceil_div(big, 256);
+            if (small > room) rounds += frac * (double)ceil_div(small - room, 256);
+            const double cost = rounds * (steps + 6.0) + plane_cost;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{8, s}; }
+        }
         if (n % 256 == 0 && !skinny) {
             const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 256) * s;
             const bool mixed = s == 1 && gemm_mixed_rem_cols(m, n) > 0;
@@ -433,6 +499,16 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             const double c0 = (double)(t0 / 512) * (steps * 0.70 + 2.3) +
                               (t0 % 512 > 256 ? steps * 0.70 + 2.3 : t0 % 512 > 0 ? steps * 0.49 + 2.3 : 0.0);
             tile = m <= 64 ? 7 : c3 <= c0 ? 3 : (m <= 256 && t0 <= 256) ? 6 : 0;
+        }
+    }
+    if (tile == 8) {  // 256x256 tiles plus a last band of 64 or 128 rows
+        const int rem_rows = gemm_rowmix_rem_rows(m, n);
+        if (rem_rows == 0) return hipErrorInvalidValue;
+        switch (mode) {
+            case GEMM_STORE_F32: return launch_rowmix<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream);
+            case GEMM_ADD_F32: return launch_rowmix<GEMM_ADD_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream);
+            case GEMM_SWIGLU_BF16: return launch_rowmix<GEMM_SWIGLU_BF16>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream);
+            default: return hipErrorInvalidValue;
         }
     }
     if (tile == 4) {  // mixed 256x256 / 256x128 launch

@@ -63,7 +63,7 @@ def test_gemm_planner_choices_are_launchable():
     """Host logic of the tile / split-K planner: whatever it picks must satisfy the launch rules of that tile
     (column multiple, split divides the 64-wide k-steps, splits only in store mode), for the stage shapes and a
     sweep of ragged row counts."""
-    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128, 7: 128}
+    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128, 7: 128, 8: 256}
     seen = set()
     for shape in synth.SHAPES.values():
         H, I = shape.hidden, shape.intermediate
@@ -81,11 +81,13 @@ def test_gemm_planner_choices_are_launchable():
                     assert splits == 1 and tile != 5
                 if tile == 7:
                     assert m <= 64
+                if tile == 8:
+                    assert m > 256 and 0 < m % 256 <= 128
                 if tile == 4:
                     tiles = ((m + 255) // 256) * (n // 256)
                     assert splits == 1 and tiles >= 256 and 0 < tiles % 256 <= 128
                 assert B.gllm_op_gemm_plan(m, n, k, mode, 8) == (tile, splits)          # deterministic
                 assert B.gllm_op_gemm_plan(m, n, k, mode, 1)[1] == 1                    # the cap is respected
-    assert {3, 6, 7}.issubset(seen)      # big problems get the 256x256 tile, few rows the deep 128x128 or the 64x128 one
+    assert {3, 6, 7, 8}.issubset(seen)   # big problems get 256x256 tiles (with a short last band where rows are left over), few rows the deep 128x128 or the 64x128 one
     with pytest.raises(B.GllmError):
         B.gllm_op_gemm_plan(128, 100, 4096, 0, 8)

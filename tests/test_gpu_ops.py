@@ -96,6 +96,51 @@ def test_gemm_256x192_tile(M, N, K):
     assert np.abs(got - 2 * ref).max() <= 4e-5 * np.abs(ref).max() + 1e-6
 
 
+@pytest.mark.parametrize("M", [257, 300, 320, 384, 600, 832])
+def test_gemm_row_mixed_launch(M):
+    """Whole bands of 256 rows as 256x256 tiles plus a last band of 64 (up to 64 rows left) or 128 rows: store, add,
+    SwiGLU and split-K planes."""
+    N, K = 768, 384
+    print(f"gemm row-mixed launch M={M}", flush=True)
+    a = rand_bits(9, 1, (M, K), 1.0)
+    w = rand_bits(9, 2, (N, K), 0.05)
+    ref = oracle.linear(oracle.bf16_to_f64(a), w)
+    Mp = (M + 255) // 256 * 256
+    da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w)
+    out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, 8)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, 8)
+    planes = torch.full((2, M, N), 9.0, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16_splitk(da, dw, planes, M, N, K, 8, 2)
+    torch.cuda.synchronize()
+    scale = np.abs(ref).max()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - 2 * ref).max() <= 4e-5 * scale + 1e-6
+    assert np.abs(planes.cpu().numpy().astype(np.float64).sum(axis=0) - ref).max() <= 2e-5 * scale + 1e-6
+    # SwiGLU: the same matrix read as 384 gate/up pairs
+    I = N // 2
+    wg, wu = rand_bits(9, 3, (I, K), 0.08), rand_bits(9, 4, (I, K), 0.08)
+    packed = np.zeros((2 * I, K), dtype=np.uint16)
+    for blk in range(I // 32):
+        packed[64 * blk: 64 * blk + 32] = wg[32 * blk: 32 * blk + 32]
+        packed[64 * blk + 32: 64 * blk + 64] = wu[32 * blk: 32 * blk + 32]
+    x = oracle.bf16_to_f64(a)
+    ref_s = oracle.swiglu(oracle.linear(x, wg), oracle.linear(x, wu))
+    act = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
+    B.gllm_op_gemm_bf16(da, to_dev_bits(packed), act, M, 2 * I, K, B.GEMM_SWIGLU_BF16, 8)
+    torch.cuda.synchronize()
+    err = np.abs(oracle.bf16_to_f64(bits_of(act)) - ref_s)
+    assert np.all(err <= np.abs(ref_s) * 2.0 ** -7 + 1e-4), float(err.max())
+
+
+def test_gemm_row_mixed_launch_refuses_shapes_without_a_short_last_band():
+    a = torch.zeros(1024, 128, dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros(256, 128, dtype=torch.bfloat16, device=DEV)
+    for M in (100, 256, 512, 400, 700):                      # no whole band, nothing left over, more than 128 rows left over
+        with pytest.raises(B.GllmError) as e:
+            B.gllm_op_gemm_bf16(a, w, torch.empty(M, 256, device=DEV), M, 256, 128, B.GEMM_STORE_F32, 8)
+        assert e.value.status == -7          # GLLM_E_UNSUPPORTED
+
+
 @pytest.mark.parametrize("tile", [-1, 4])
 @pytest.mark.parametrize("mode", ["store", "swiglu"])
 def test_gemm_mixed_tile_launch(mode, tile):
