@@ -52,6 +52,7 @@ class _Slot:
     picked: object
     picked_host: object
     event: object
+    staged: object               # the layers of the micro-batch are done (what the second stream waits for)
     begin: object                # timed event in front of the micro-batch (timing mode)
     batch_id: int = -1
     rows: List[Tuple[int, int, int]] = field(default_factory=list)
@@ -62,9 +63,12 @@ class _Slot:
 class Engine:
     def __init__(self, shape: synth.StageShape, vocab: int, params: sched.Params, *, max_batch_tokens: int,
                  max_batch_seqs: int, max_context: int, device: str = "cuda", max_in_flight: Optional[int] = None,
-                 timing: bool = False):
+                 timing: bool = False, overlap_head: bool = True):
         """max_in_flight: micro-batches enqueued before the oldest is waited for (default and at most #PP_depth;
-        1 makes the loop synchronous).  timing: bracket every micro-batch with timed events (stats["gpu_ms"])."""
+        1 makes the loop synchronous).  timing: bracket every micro-batch with timed events (stats["gpu_ms"]; the
+        brackets of consecutive micro-batches overlap when overlap_head is on).  overlap_head: the last-stage extras
+        of a micro-batch (projection, sampler, read-back) run on a second stream, next to the layers of the
+        micro-batch after it -- they only read the finished micro-batch's own output buffer."""
         import torch
         self.torch = torch
         self.shape, self.vocab, self.params, self.device = shape, vocab, params, device
@@ -83,6 +87,7 @@ class Engine:
         self.requests: Dict[int, _Request] = {}
         self.flying: deque = deque()
         self.timing = timing
+        self.tail = torch.cuda.Stream() if overlap_head else None
         depth = params.pp_depth if max_in_flight is None else max(1, min(max_in_flight, params.pp_depth))
         self.free_slots = [self._make_slot() for _ in range(depth)]
         self.observer: Optional[Callable] = None     # tests: called with the slot of every retired micro-batch
@@ -99,7 +104,7 @@ class Engine:
             par_host=pin(5, S, dtype=t.int32).zero_(), par=t.zeros(5, S, dtype=t.int32, device=dev),
             logits=t.empty(S, self.head.padded_vocab, dtype=t.float32, device=dev),
             picked=t.empty(S, dtype=t.int32, device=dev), picked_host=pin(S, dtype=t.int32),
-            event=t.cuda.Event(enable_timing=self.timing), begin=t.cuda.Event(enable_timing=True) if self.timing else None)
+            event=t.cuda.Event(enable_timing=self.timing), staged=t.cuda.Event(), begin=t.cuda.Event(enable_timing=True) if self.timing else None)
 
     # ---- set-up -----------------------------------------------------------------------------------------------
     def load(self, layers: Sequence[Dict[str, object]], embedding_table, final_norm_gain, w_vocab) -> None:
@@ -162,13 +167,19 @@ class Engine:
         head.gllm_op_embedding(slot.ids[:T], self.table, slot.x[:T])
         self.stage.forward(nt, cl, bt, slot.x, slot.out, slot.out32)
         if m:
-            slot.par.copy_(slot.par_host, non_blocking=True)
-            reals_dev = slot.par.view(t.float32)
-            self.head.logits(slot.out32[:T], slot.par[0, :m], slot.logits[:m])
-            head.gllm_op_sample(slot.logits[:m], self.vocab, reals_dev[2, :m], slot.par[1, :m], reals_dev[3, :m], reals_dev[4, :m],
-                                slot.picked[:m])
-            slot.picked_host[:m].copy_(slot.picked[:m], non_blocking=True)
-        slot.event.record()
+            if self.tail is not None:
+                slot.staged.record()
+                self.tail.wait_event(slot.staged)
+            with t.cuda.stream(self.tail if self.tail is not None else t.cuda.current_stream()):
+                slot.par.copy_(slot.par_host, non_blocking=True)
+                reals_dev = slot.par.view(t.float32)
+                self.head.logits(slot.out32[:T], slot.par[0, :m], slot.logits[:m])
+                head.gllm_op_sample(slot.logits[:m], self.vocab, reals_dev[2, :m], slot.par[1, :m], reals_dev[3, :m],
+                                    reals_dev[4, :m], slot.picked[:m])
+                slot.picked_host[:m].copy_(slot.picked[:m], non_blocking=True)
+                slot.event.record()
+        else:
+            slot.event.record()
         slot.batch_id, slot.rows, slot.takers, slot.num_tokens = bid, rows, takers, T
         self.flying.append(slot)
         self.stats["micro_batches"] += 1
