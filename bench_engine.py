@@ -6,11 +6,13 @@ stage standing for the whole model (hidden 4096, vocabulary 128256, random weigh
     python bench_engine.py [--requests N] [--seed S]
 
 Prints one JSON line.  `value` = generated tokens per second (wall clock, everything included: scheduling, block
-tables, token-id upload, the kernels, the read-back of the sampled ids) with up to #PP_depth micro-batches enqueued ahead;
-`enqueued_ahead_one_stream` keeps the last-stage extras of a micro-batch on the same stream as the layers (the default
-runs them on a second stream, next to the layers of the following micro-batch); `synchronous` also keeps only one
-micro-batch in flight, i.e. exposes the host work; `gpu_busy` is the sum of the micro-batches' own event-timed
-durations over the wall time (above 1 when they overlap).  All requests are present at the start;
+tables, token-id upload, the kernels, the read-back of the sampled ids) in the engine's default arrangement (`two_lanes`):
+up to #PP_depth micro-batches enqueued ahead, consecutive micro-batches on two streams through two stage objects over
+one set of weights, the last-stage extras of each on a further stream.  `enqueued_ahead` runs all layers on one stream
+(extras still beside them); `enqueued_ahead_one_stream` keeps the extras on that stream too; `synchronous` also keeps only
+one micro-batch in flight, i.e. exposes the host work; `gpu_busy` is the sum of the micro-batches' own event-timed
+durations over the wall time (above 1 when they overlap).  --try-lanes N... times further lane counts.
+All requests are present at the start;
 prompt and output lengths are log-normal (medians 220 and 64), a stand-in for a chat workload.
 `serving` replays the same requests with Poisson arrivals at --rate requests per second (wall clock) and reports the
 latency metrics of the paper's section 4.1: time to first token, time per output token, end-to-end latency.
@@ -32,6 +34,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--requests", type=int, default=1024)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--try-lanes", type=int, nargs="*", default=[], help="experiment: further lane counts to time")
     ap.add_argument("--rate", type=float, default=100.0, help="arrivals per second of the serving run (0: skip it)")
     args = ap.parse_args()
     dev = "cuda:0"
@@ -51,9 +54,10 @@ def main():
     params = S.Params(policy=S.TOKEN_THROTTLING, iters_t=8, max_p=2048, min_p=32, kv_thresh_bp=500, pp_depth=4,
                       token_budget=2048, total_pages=32768)
 
-    def run(max_in_flight, overlap_head=True):
+    def run(max_in_flight, overlap_head=True, lanes=2):
         eng = E.Engine(shape, V, params, max_batch_tokens=2048 + args.requests, max_batch_seqs=args.requests + 8,
-                       max_context=2048 + 256, device=dev, max_in_flight=max_in_flight, timing=True, overlap_head=overlap_head)
+                       max_context=2048 + 256, device=dev, max_in_flight=max_in_flight, timing=True, overlap_head=overlap_head,
+                       lanes=lanes)
         eng.load(layers, table, gain, w_vocab)
         for i, (p, o) in enumerate(reqs):
             eng.add_request(i, p, o, E.Sampling(temperature=0.8, top_k=50, top_p=0.95, seed=i))
@@ -108,17 +112,19 @@ def main():
                 "e2e_ms": {"mean": round(1e3 * sum(e2e) / len(e2e), 2), "p50": pct(e2e, 0.5), "p99": pct(e2e, 0.99)}}
 
     run(None)                                               # warm-up: first-use costs of every kernel
-    ahead = run(None)
-    one_stream = run(None, overlap_head=False)
-    sync = run(1, overlap_head=False)
+    two_lanes = run(None)
+    ahead = run(None, lanes=1)
+    more = {n: run(None, lanes=n) for n in args.try_lanes}
+    one_stream = run(None, overlap_head=False, lanes=1)
+    sync = run(1, overlap_head=False, lanes=1)
     print(json.dumps({
         "metric": "generated tokens per second, closed loop on one GPU (scheduler + embedding + stage + head + sampler)",
-        "value": ahead["generated_tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",
+        "value": two_lanes["generated_tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.requests} requests at once, 8 layers of the Llama-3-8B shape as the whole model, vocabulary {V}",
                    "prompt_tokens": sum(len(p) for p, _ in reqs), "output_tokens": sum(o for _, o in reqs),
                    "scheduler": "token throttling T=8 MaxP=2048 MinP=32 KV_thresh=0.05 depth=4", "sampling": "temperature 0.8, top-k 50, top-p 0.95"},
-        "enqueued_ahead": ahead, "enqueued_ahead_one_stream": one_stream, "synchronous": sync, "serving": serve(args.rate) if args.rate > 0 else None}))
+        "two_lanes": two_lanes, "enqueued_ahead": ahead, **{f"lanes_{n}": v for n, v in more.items()}, "enqueued_ahead_one_stream": one_stream, "synchronous": sync, "serving": serve(args.rate) if args.rate > 0 else None}))
 
 
 if __name__ == "__main__":

@@ -131,6 +131,15 @@ gllm_status gllm_stage_load_layer(gllm_stage* stage, int32_t layer, const gllm_l
 gllm_status gllm_stage_bind_kv_pool(gllm_stage* stage, void* k_pool /*DEVICE*/, void* v_pool /*DEVICE*/,
                                     int64_t num_blocks);
 
+/* Several stage objects over one set of weights: `stage` gives up its own (repacked) weight buffers and uses those
+ * of `owner` from now on -- for running micro-batches on several streams, one stage object per stream (each has its
+ * own workspace, metadata buffers and internal streams; calls on one object are still not thread-safe), without a
+ * copy of the weights per stream.  Both must have been created with the same layer shapes; every layer of `owner`
+ * must be loaded; `owner` must stay alive, and its weights unchanged, as long as `stage` is used.  Synchronises the
+ * device.  GLLM_E_INVALID for differing shapes or an owner that borrows itself, GLLM_E_STATE for an owner with
+ * unloaded layers; afterwards gllm_stage_load_layer on `stage` gives GLLM_E_STATE. */
+gllm_status gllm_stage_share_weights(gllm_stage* stage, const gllm_stage* owner);
+
 /* Debug option: when nonzero, forward() also rejects batches in which two different
  * (sequence, logical page) pairs that receive new tokens name the same physical page. */
 gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);

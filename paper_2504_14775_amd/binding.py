@@ -23,7 +23,7 @@ GEMM_STORE_F32, GEMM_ADD_F32, GEMM_SWIGLU_BF16 = 0, 1, 2
 EXPORTS = [
     "gllm_stage_create", "gllm_stage_destroy", "gllm_last_error", "gllm_status_name",
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
-    "gllm_stage_bind_kv_pool", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
+    "gllm_stage_bind_kv_pool", "gllm_stage_share_weights", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
     "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_gemm_plan", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
 ]
@@ -91,6 +91,8 @@ def load_library():
     lib.gllm_stage_bind_kv_pool.argtypes = [vp, vp, vp, i64]
     lib.gllm_stage_set_alias_check.restype = i32
     lib.gllm_stage_set_alias_check.argtypes = [vp, i32]
+    lib.gllm_stage_share_weights.restype = i32
+    lib.gllm_stage_share_weights.argtypes = [vp, vp]
     lib.gllm_stage_set_option.restype = i32
     lib.gllm_stage_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.gllm_stage_forward.restype = i32
@@ -180,6 +182,11 @@ class Stage:
     def bind_kv_pool(self, k_pool, v_pool, num_blocks: int) -> None:
         self._check(self.lib.gllm_stage_bind_kv_pool(self.handle, k_pool.data_ptr(), v_pool.data_ptr(), num_blocks))
         self._pool = (k_pool, v_pool)
+
+    def share_weights(self, owner: "Stage") -> None:
+        """Use owner's loaded weights instead of a copy of one's own (owner must outlive this stage)."""
+        self._check(self.lib.gllm_stage_share_weights(self.handle, owner.handle))
+        self._owner = owner
 
     def set_alias_check(self, on: bool) -> None:
         self._check(self.lib.gllm_stage_set_alias_check(self.handle, int(on)))

@@ -55,6 +55,7 @@ struct gllm_stage {
     int64_t m_pad = 0;
     int max_items = 0, max_pre_items = 0, pre_rows = 64;
     std::vector<LayerBuffers> layers;
+    bool borrowed_weights = false;  // the layer buffers belong to another stage (gllm_stage_share_weights)
     float* rope_cs = nullptr;  // device [max_position][d/2][2]
     // workspace
     void* ws = nullptr;
@@ -293,10 +294,11 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
 void gllm_stage_destroy(gllm_stage* s) {
     if (!s) return;
     (void)hipDeviceSynchronize();
-    for (auto& L : s->layers) {
-        bf16_t* ps[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2, L.bias};
-        for (bf16_t* p : ps) if (p) (void)hipFree(p);
-    }
+    if (!s->borrowed_weights)
+        for (auto& L : s->layers) {
+            bf16_t* ps[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2, L.bias};
+            for (bf16_t* p : ps) if (p) (void)hipFree(p);
+        }
     if (s->rope_cs) (void)hipFree(s->rope_cs);
     if (s->meta_dev) (void)hipFree(s->meta_dev);
     for (int i = 0; i < kStagingSlots; ++i) {
@@ -327,6 +329,7 @@ gllm_status gllm_stage_bind_workspace(gllm_stage* s, void* workspace, size_t byt
 gllm_status gllm_stage_load_layer(gllm_stage* s, int32_t layer, const gllm_layer_weights* w, void* stream_) {
     if (!s) return GLLM_E_INVALID;
     if (!w || layer < 0 || layer >= s->cfg.num_layers) return fail(s, GLLM_E_INVALID, "bad layer index or null weights");
+    if (s->borrowed_weights) return fail(s, GLLM_E_STATE, "this stage borrows its weights: load them into the owner");
     const gllm_stage_config& c = s->cfg;
     if (!w->wq || !w->wk || !w->wv || !w->wo || !w->wgate || !w->wup || !w->wdown || !w->norm1 || !w->norm2)
         return fail(s, GLLM_E_INVALID, "null weight pointer");
@@ -348,6 +351,27 @@ gllm_status gllm_stage_load_layer(gllm_stage* s, int32_t layer, const gllm_layer
         HIP_TRY(s, hipMemcpyAsync(L.bias + s->q_dim + s->kv_dim, w->bv, (size_t)s->kv_dim * 2, hipMemcpyDeviceToDevice, st));
     }
     L.loaded = true;
+    return GLLM_OK;
+}
+
+gllm_status gllm_stage_share_weights(gllm_stage* s, const gllm_stage* owner) {
+    if (!s) return GLLM_E_INVALID;
+    if (!owner || owner == s) return fail(s, GLLM_E_INVALID, "no owner stage");
+    const gllm_stage_config &a = s->cfg, &b = owner->cfg;
+    if (a.num_layers != b.num_layers || a.hidden != b.hidden || a.n_q_heads != b.n_q_heads || a.n_kv_heads != b.n_kv_heads ||
+        a.head_dim != b.head_dim || a.intermediate != b.intermediate || (a.has_qkv_bias != 0) != (b.has_qkv_bias != 0))
+        return fail(s, GLLM_E_INVALID, "the two stages differ in their layer shapes");
+    if (owner->borrowed_weights) return fail(s, GLLM_E_INVALID, "the owner stage borrows its weights itself");
+    for (const LayerBuffers& L : owner->layers)
+        if (!L.loaded) return fail(s, GLLM_E_STATE, "the owner stage has layers without weights");
+    HIP_TRY(s, hipDeviceSynchronize());  // nothing of this stage may still read the buffers that are freed now
+    if (!s->borrowed_weights)
+        for (auto& L : s->layers) {
+            bf16_t* ps[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2, L.bias};
+            for (bf16_t* p : ps) if (p) (void)hipFree(p);
+        }
+    s->layers = owner->layers;
+    s->borrowed_weights = true;
     return GLLM_OK;
 }
 

@@ -63,26 +63,43 @@ class _Slot:
 class Engine:
     def __init__(self, shape: synth.StageShape, vocab: int, params: sched.Params, *, max_batch_tokens: int,
                  max_batch_seqs: int, max_context: int, device: str = "cuda", max_in_flight: Optional[int] = None,
-                 timing: bool = False, overlap_head: bool = True):
+                 timing: bool = False, overlap_head: bool = True, lanes: Optional[int] = None):
         """max_in_flight: micro-batches enqueued before the oldest is waited for (default and at most #PP_depth;
         1 makes the loop synchronous).  timing: bracket every micro-batch with timed events (stats["gpu_ms"]; the
         brackets of consecutive micro-batches overlap when overlap_head is on).  overlap_head: the last-stage extras
         of a micro-batch (projection, sampler, read-back) run on a second stream, next to the layers of the
-        micro-batch after it -- they only read the finished micro-batch's own output buffer."""
+        micro-batch after it -- they only read the finished micro-batch's own output buffer.  lanes (default 2 where
+        #PP_depth allows, at most #PP_depth): 2 runs the
+        layers of consecutive micro-batches on two streams through two stage objects (each with its own workspace,
+        sharing one set of weights, both bound to the one KV pool): micro-batches in flight never share a
+        request and only read shared prefix pages, so they are independent, and the gaps between the dependent
+        kernels of one are filled by the kernels of the other."""
         import torch
         self.torch = torch
         self.shape, self.vocab, self.params, self.device = shape, vocab, params, device
         self.max_tokens, self.max_seqs, self.max_context = max_batch_tokens, max_batch_seqs, max_context
         self.max_blocks = -(-max_context // PAGE)
         self.sched = sched.Scheduler(params)
-        self.stage = binding.Stage(binding.make_config(shape, max_batch_tokens, max_batch_seqs, self.max_blocks, max_context))
-        self._ws = torch.empty(self.stage.workspace_bytes(), dtype=torch.uint8, device=device)
-        self.stage.bind_workspace(self._ws)
+        if lanes is None:
+            lanes = min(2, max(1, params.pp_depth))
+        if not 1 <= lanes <= max(1, params.pp_depth):
+            raise ValueError("lanes must be between 1 and #PP_depth")
+        self.stages, self._ws = [], []
+        for _ in range(lanes):
+            st = binding.Stage(binding.make_config(shape, max_batch_tokens, max_batch_seqs, self.max_blocks, max_context))
+            ws = torch.empty(st.workspace_bytes(), dtype=torch.uint8, device=device)
+            st.bind_workspace(ws)
+            self.stages.append(st)
+            self._ws.append(ws)
+        self.stage = self.stages[0]
+        self.lane_streams = [torch.cuda.Stream() for _ in range(lanes)] if lanes > 1 else [None]
+        self.launched = 0
         self.head = head.Head(shape.hidden, vocab, max_batch_seqs, shape.rms_eps, device=device)
         n_el = shape.num_layers * synth.pool_elems_per_layer(shape, params.total_pages)
         self.k_pool = torch.zeros(n_el, dtype=torch.bfloat16, device=device)
         self.v_pool = torch.zeros(n_el, dtype=torch.bfloat16, device=device)
-        self.stage.bind_kv_pool(self.k_pool, self.v_pool, params.total_pages)
+        for st in self.stages:
+            st.bind_kv_pool(self.k_pool, self.v_pool, params.total_pages)
         self.table = None
         self.requests: Dict[int, _Request] = {}
         self.flying: deque = deque()
@@ -111,7 +128,10 @@ class Engine:
         """layers: per layer the device tensors gllm_stage_load_layer takes; embedding_table: bf16 [vocab, hidden];
         final_norm_gain: bf16 [hidden]; w_vocab: bf16 [vocab, hidden].  The table is used in place (keep it alive)."""
         for l, w in enumerate(layers):
-            self.stage.load_layer(l, w)
+            self.stages[0].load_layer(l, w)
+        self.torch.cuda.synchronize()
+        for st in self.stages[1:]:
+            st.share_weights(self.stages[0])
         self.head.load(final_norm_gain, w_vocab)
         self.table = embedding_table
         self.torch.cuda.synchronize()
@@ -161,16 +181,23 @@ class Engine:
                 words[1, j] = r.sampling.top_k
                 reals[2, j], reals[3, j] = r.sampling.temperature, r.sampling.top_p
                 reals[4, j] = r.rng.random(dtype=np.float32) if r.sampling.temperature > 0 else 0.0
-        if self.timing:
-            slot.begin.record()
-        slot.ids[:T].copy_(slot.ids_host[:T], non_blocking=True)
-        head.gllm_op_embedding(slot.ids[:T], self.table, slot.x[:T])
-        self.stage.forward(nt, cl, bt, slot.x, slot.out, slot.out32)
+        lane = self.launched % len(self.stages)
+        self.launched += 1
+        main = self.lane_streams[lane] if self.lane_streams[lane] is not None else t.cuda.current_stream()
+        with t.cuda.stream(main):
+            if self.timing:
+                slot.begin.record()
+            slot.ids[:T].copy_(slot.ids_host[:T], non_blocking=True)
+            head.gllm_op_embedding(slot.ids[:T], self.table, slot.x[:T])
+            self.stages[lane].forward(nt, cl, bt, slot.x, slot.out, slot.out32)
+            if m and self.tail is not None:
+                slot.staged.record()
+            if not m:
+                slot.event.record()
         if m:
             if self.tail is not None:
-                slot.staged.record()
                 self.tail.wait_event(slot.staged)
-            with t.cuda.stream(self.tail if self.tail is not None else t.cuda.current_stream()):
+            with t.cuda.stream(self.tail if self.tail is not None else main):
                 slot.par.copy_(slot.par_host, non_blocking=True)
                 reals_dev = slot.par.view(t.float32)
                 self.head.logits(slot.out32[:T], slot.par[0, :m], slot.logits[:m])
@@ -178,8 +205,6 @@ class Engine:
                                     reals_dev[4, :m], slot.picked[:m])
                 slot.picked_host[:m].copy_(slot.picked[:m], non_blocking=True)
                 slot.event.record()
-        else:
-            slot.event.record()
         slot.batch_id, slot.rows, slot.takers, slot.num_tokens = bid, rows, takers, T
         self.flying.append(slot)
         self.stats["micro_batches"] += 1
@@ -231,4 +256,5 @@ class Engine:
     def close(self) -> None:
         self.torch.cuda.synchronize()
         self.head.destroy()
-        self.stage.destroy()
+        for st in reversed(self.stages):             # the borrowers first, the owner of the weights last
+            st.destroy()

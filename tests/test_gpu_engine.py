@@ -20,10 +20,10 @@ from helpers import layer_weights_np
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("pages,depth,caching,sampled", [(64, 3, False, False), (7, 2, False, False), (64, 2, True, False),
-                                                         (64, 2, False, True)])
-def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sampled):
-    print(f"engine: pool of {pages} pages, depth {depth}, prefix caching {caching}, sampling {sampled}", flush=True)
+@pytest.mark.parametrize("pages,depth,caching,sampled,lanes", [(64, 3, False, False, 1), (7, 2, False, False, 1), (64, 2, True, False, 1),
+                                                               (64, 2, False, True, 1), (64, 4, False, False, 2), (7, 2, True, False, 2)])
+def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sampled, lanes):
+    print(f"engine: pool of {pages} pages, depth {depth}, prefix caching {caching}, sampling {sampled}, {lanes} lane(s)", flush=True)
     shape = dataclasses.replace(synth.SHAPES["tiny"], num_layers=2, name="tiny_engine")
     V, H = 300, shape.hidden
     rng = np.random.default_rng(9)
@@ -37,7 +37,7 @@ def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sample
     w = layer_weights_np(shape, 51)
     params = S.Params(policy=S.TOKEN_THROTTLING, iters_t=2, max_p=48, min_p=4, kv_thresh_bp=0 if pages < 64 else 500,
                       pp_depth=depth, token_budget=40, total_pages=pages, prefix_caching=caching)
-    eng = E.Engine(shape, V, params, max_batch_tokens=64, max_batch_seqs=8, max_context=192)
+    eng = E.Engine(shape, V, params, max_batch_tokens=64, max_batch_seqs=8, max_context=192, lanes=lanes)
     d_table = to_dev_bits(table)
     eng.load([{k: to_dev_bits(v) for k, v in lw.items()} for lw in w], d_table, to_dev_bits(gain), to_dev_bits(w_lm))
     n_el = shape.num_layers * synth.pool_elems_per_layer(shape, pages)
@@ -89,7 +89,7 @@ def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sample
     for r in late:
         eng.add_request(r, prompts[r], out_len[r])
         result = eng.run()
-    if caching:
+    if caching and pages >= 64:
         # a follow-up that repeats a finished conversation: the pages of the answer are found as well
         before = eng.sched.state()["prefix_hit_tokens"]
         talk = prompts[1] + result[1]                       # 70 prompt tokens + 9 answer tokens
@@ -102,9 +102,9 @@ def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sample
     assert {r: len(t) for r, t in result.items()} == dict(enumerate(out_len))
     assert st["free_pages"] == pages and st["batches_in_flight"] == 0
     assert worst["max_flying"] == depth                     # micro-batches really were enqueued ahead
-    if pages < 64:
+    if pages < 64 and not caching:
         assert st["preemptions"] > 0
-    if caching:
+    if caching and pages >= 64:
         assert st["prefix_hit_tokens"] >= 32                # the second prompt found the first one's stem
     for r, toks in result.items():
         assert all(0 <= t < V for t in toks)

@@ -291,3 +291,43 @@ def test_head_group_shapes(n_q, n_kv, d):
     mk, mv = written_mask(shape, batch)
     check_pool("K", r["gk"], kp0, r["kp"], shape.num_layers, mask=mk)
     check_pool("V", r["gv"], vp0, r["vp"], shape.num_layers, mask=mv)
+
+
+def test_two_stage_objects_over_one_set_of_weights():
+    """A stage that borrows another's weights gives bit-identical outputs and pools, refuses weights of its own
+    afterwards, and refuses an owner of another shape or one that is not fully loaded."""
+    print("shared weights", flush=True)
+    shape = dataclasses.replace(synth.SHAPES["tiny"], num_layers=2, name="tiny_two_layers")
+    batch = synth.make_batch("tiny", 4)
+    w = layer_weights_np(shape, 4)
+    kp0, vp0 = pool_np(shape, 4, batch.num_blocks)
+    x = to_dev_bits(hidden_np(shape, 4, batch.num_tokens))
+    owner = GpuStage(shape, w, [batch])
+    borrower = B.stage_for_batches(shape, [batch])
+    other = B.stage_for_batches(dataclasses.replace(shape, intermediate=shape.intermediate + 128), [batch])
+    unloaded = B.stage_for_batches(shape, [batch])
+    for bad, code in ((other, -1), (unloaded, -5), (borrower, -1)):
+        with pytest.raises(B.GllmError) as e:
+            borrower.share_weights(bad)
+        assert e.value.status == code, borrower.last_error()
+    borrower.share_weights(owner.stage)
+    with pytest.raises(B.GllmError) as e:
+        unloaded.share_weights(borrower)                      # no chains of borrowers
+    assert e.value.status == -1
+    with pytest.raises(B.GllmError) as e:
+        borrower.load_layer(0, {k: to_dev_bits(v) for k, v in w[0].items()})
+    assert e.value.status == -5
+    got = []
+    for st in (owner.stage, borrower):
+        dk, dv = to_dev_bits(kp0), to_dev_bits(vp0)
+        out = torch.empty(batch.num_tokens, shape.hidden, dtype=torch.bfloat16, device=DEV)
+        st.bind_kv_pool(dk, dv, batch.num_blocks)
+        st.forward(batch.new_tokens, batch.cached_len, batch.block_tables, x, out)
+        torch.cuda.synchronize()
+        got.append((bits_of(out), bits_of(dk), bits_of(dv)))
+    for a, b in zip(*got):
+        assert np.array_equal(a, b)
+    borrower.destroy()                                        # must leave the owner's buffers alone
+    dk, dv = to_dev_bits(kp0), to_dev_bits(vp0)
+    out, _ = owner.run(batch, dk, dv, x, want_f32=False)
+    assert np.array_equal(bits_of(out), got[0][0])
