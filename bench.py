@@ -7,7 +7,8 @@ path, inputs (weights, KV pool, hidden states) already resident in HBM; only the
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llama3_8b_pp4] [--no-cpu-baseline]
 
-Prints ONE JSON line.  `roofline` describes the bf16 MFMA GEMM kernel (all four projections of a
+Eight untimed passes belong to the set-up (first-use costs), then W warm-up steps, then K timed steps between two
+device synchronisations.  Prints ONE JSON line.  `roofline` describes the bf16 MFMA GEMM kernel (all four projections of a
 layer are launches of it), measured with HIP events on the launch stream in a second pass of the
 same steps; `roofline_decode_attention` gives the HBM figure of the decode attention kernel;
 `cpu_baseline` times the CPU oracle on a bounded sample of the same batch.
@@ -52,7 +53,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="llama3_8b_pp4")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-index", type=int, default=0, help="batch of the 70B-shaped series")
@@ -129,6 +130,11 @@ def main():
     def step():
         stage.forward(batch.new_tokens, batch.cached_len, batch.block_tables, hidden, out)
 
+    # first-use costs (code objects, every metadata staging slot, the clocks coming up from idle) are paid here, as
+    # part of the set-up: with fewer than about eight passes before the timed region they add 10-20 ms to it
+    for _ in range(8):
+        step()
+    torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -97,8 +97,8 @@ typedef struct {
     const int32_t* block_tables;
 } gllm_batch;
 
-/* Creates a stage on the current HIP device: allocates the library-owned copies of the
- * weights (filled by gllm_stage_load_layer), the RoPE table and the metadata staging. */
+/* Creates a stage on the current HIP device: allocates the RoPE table and the metadata staging.  The
+ * library-owned copies of a layer's weights are allocated when gllm_stage_load_layer first fills them. */
 gllm_status gllm_stage_create(const gllm_stage_config* cfg /*HOST*/, gllm_stage** out /*HOST*/);
 void gllm_stage_destroy(gllm_stage* stage);
 

@@ -108,6 +108,36 @@ gllm_status hip_fail(gllm_stage* s, hipError_t e, const char* what) {
     return fail(s, GLLM_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+void free_layer(LayerBuffers& L) {
+    bf16_t** ps[] = {&L.wqkv, &L.wo, &L.wgu, &L.wd, &L.norm1, &L.norm2, &L.bias};
+    for (bf16_t** p : ps) {
+        if (*p) (void)hipFree(*p);
+        *p = nullptr;
+    }
+    L.loaded = false;
+}
+
+// The repacked weights of one layer, zero filled (on the stream that will fill them) so that the padding is zero.
+hipError_t alloc_layer(const gllm_stage* s, LayerBuffers& L, hipStream_t st) {
+    const gllm_stage_config& c = s->cfg;
+    struct { bf16_t** p; size_t n; } bufs[] = {
+        {&L.wqkv, (size_t)s->n_qkv_pad * c.hidden},
+        {&L.wo, (size_t)s->hidden_pad_n * s->q_dim},
+        {&L.wgu, (size_t)2 * s->inter_pad * c.hidden},
+        {&L.wd, (size_t)s->hidden_pad_n * s->inter_pad},
+        {&L.norm1, (size_t)c.hidden}, {&L.norm2, (size_t)c.hidden},
+        {&L.bias, (size_t)s->n_qkv_pad}};
+    for (auto& b : bufs) {
+        hipError_t e = hipMalloc((void**)b.p, b.n * 2);
+        if (e == hipSuccess) e = hipMemsetAsync(*b.p, 0, b.n * 2, st);
+        if (e != hipSuccess) {
+            free_layer(L);
+            return e;
+        }
+    }
+    return hipSuccess;
+}
+
 #define HIP_TRY(stage, call)                                   \
     do {                                                       \
         hipError_t _e = (call);                                \
@@ -232,20 +262,7 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
         gllm_stage_destroy(s);
         return st;
     };
-    // weights (zero filled so that the padding is zero)
-    for (auto& L : s->layers) {
-        struct { bf16_t** p; size_t n; } bufs[] = {
-            {&L.wqkv, (size_t)s->n_qkv_pad * c.hidden},
-            {&L.wo, (size_t)s->hidden_pad_n * s->q_dim},
-            {&L.wgu, (size_t)2 * s->inter_pad * c.hidden},
-            {&L.wd, (size_t)s->hidden_pad_n * s->inter_pad},
-            {&L.norm1, (size_t)c.hidden}, {&L.norm2, (size_t)c.hidden},
-            {&L.bias, (size_t)s->n_qkv_pad}};
-        for (auto& b : bufs) {
-            if ((e = hipMalloc((void**)b.p, b.n * 2)) != hipSuccess) return bail(e, "hipMalloc(weights)");
-            if ((e = hipMemset(*b.p, 0, b.n * 2)) != hipSuccess) return bail(e, "hipMemset(weights)");
-        }
-    }
+    // (the weight buffers of a layer are allocated when the layer is first loaded)
     // RoPE table: angle = pos * theta^(-2j/d), formed in double
     {
         const int half = c.head_dim / 2;
@@ -295,10 +312,7 @@ void gllm_stage_destroy(gllm_stage* s) {
     if (!s) return;
     (void)hipDeviceSynchronize();
     if (!s->borrowed_weights)
-        for (auto& L : s->layers) {
-            bf16_t* ps[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2, L.bias};
-            for (bf16_t* p : ps) if (p) (void)hipFree(p);
-        }
+        for (auto& L : s->layers) free_layer(L);
     if (s->rope_cs) (void)hipFree(s->rope_cs);
     if (s->meta_dev) (void)hipFree(s->meta_dev);
     for (int i = 0; i < kStagingSlots; ++i) {
@@ -337,6 +351,7 @@ gllm_status gllm_stage_load_layer(gllm_stage* s, int32_t layer, const gllm_layer
     hipStream_t st = (hipStream_t)stream_;
     LayerBuffers& L = s->layers[layer];
     const int H = c.hidden;
+    if (!L.wqkv) HIP_TRY(s, alloc_layer(s, L, st));
     HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wq, s->q_dim, H, L.wqkv, H, 0, st));
     HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wk, s->kv_dim, H, L.wqkv, H, s->q_dim, st));
     HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wv, s->kv_dim, H, L.wqkv, H, s->q_dim + s->kv_dim, st));
@@ -366,10 +381,7 @@ gllm_status gllm_stage_share_weights(gllm_stage* s, const gllm_stage* owner) {
         if (!L.loaded) return fail(s, GLLM_E_STATE, "the owner stage has layers without weights");
     HIP_TRY(s, hipDeviceSynchronize());  // nothing of this stage may still read the buffers that are freed now
     if (!s->borrowed_weights)
-        for (auto& L : s->layers) {
-            bf16_t* ps[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2, L.bias};
-            for (bf16_t* p : ps) if (p) (void)hipFree(p);
-        }
+        for (auto& L : s->layers) free_layer(L);
     s->layers = owner->layers;
     s->borrowed_weights = true;
     return GLLM_OK;
