@@ -577,7 +577,11 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         bt_off += pages;
         row += n;
     }
-    // launch order of the decode items: longest first, so that the last workgroups to start are the shortest
+    // launch order, both kinds of attention: longest first, so that the last workgroups to start are the shortest
+    // (a chunk deep in a long prompt attends to many times the keys of a chunk that starts one)
+    std::stable_sort(pre_items, pre_items + n_pre, [](const PrefillItem& x, const PrefillItem& y) {
+        return x.pos0 + x.n_rows > y.pos0 + y.n_rows;
+    });
     for (int i = 0; i < n_items; ++i) dec_order[i] = i;
     std::stable_sort(dec_order, dec_order + n_items, [&](int32_t x, int32_t y) {
         return dec_items[x].kv_end - dec_items[x].kv_begin > dec_items[y].kv_end - dec_items[y].kv_begin;

@@ -19,7 +19,9 @@ from paper_2504_14775_amd import binding as B
 from paper_2504_14775_amd import synth
 from gpu_util import DEV, bits_of, parity_report
 
-pytestmark = pytest.mark.gpu
+# the oracle's sample takes one to two minutes of CPU time at the larger shapes: these tests carry their own time
+# limit, which takes precedence over a shorter one given on the command line
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
 def slot_checksums(shape, pool, num_blocks, which):
