@@ -66,6 +66,11 @@ hipError_t launch_copy_rows_padded(const bf16_t* src, int rows, int cols, bf16_t
 hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, int hidden, bf16_t* dst,
                                int64_t ld_dst, hipStream_t stream);
 
+// A run of consecutive new tokens of one sequence that fall into one page: rows row0 .. row0 + n - 1 go to slots
+// slot0 .. slot0 + n - 1 of `page`.
+struct VTile {
+    int32_t row0, n, page, slot0;
+};
 struct RopeKvArgs {
     const float* qkv;        // planes x [T][ld_qkv] fp32: q heads, then k heads, then v heads; planes are summed
     int64_t ld_qkv;
@@ -80,6 +85,12 @@ struct RopeKvArgs {
     bf16_t* k_pool;          // this layer's K pool
     bf16_t* v_pool;          // this layer's V pool
     int T, n_q, n_kv, d;
+    // V of the rows listed in v_tiles (runs of new tokens inside one page) is written by extra workgroups, one per
+    // (run, KV head), in 16-byte pieces of 8 slots; a token workgroup writes its own V only where tok_own_v says so (a run
+    // of one: a decode row).  Without v_tiles every token writes its own V.
+    const VTile* v_tiles;
+    int n_vtiles;
+    const int32_t* tok_own_v;  // [T], nonzero: the token's workgroup writes its V
 };
 hipError_t launch_rope_kv_write(const RopeKvArgs& a, hipStream_t stream);
 

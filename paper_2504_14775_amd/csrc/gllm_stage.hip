@@ -41,7 +41,7 @@ constexpr int kStagingSlots = 4;
 constexpr int kMaxSplits = kMaxPlanes;
 
 struct MetaLayout {  // offsets in bytes inside the metadata block (host staging and device copy alike)
-    size_t tok_pos, tok_page, bt_flat, dec_items, dec_order, dec_rows, pre_items, total;
+    size_t tok_pos, tok_page, tok_own_v, bt_flat, dec_items, dec_order, dec_rows, pre_items, v_tiles, total;
 };
 
 }  // namespace
@@ -53,7 +53,7 @@ struct gllm_stage {
     // derived sizes
     int q_dim = 0, kv_dim = 0, n_qkv = 0, n_qkv_pad = 0, inter_pad = 0, hidden_pad_n = 0;
     int64_t m_pad = 0;
-    int max_items = 0, max_pre_items = 0, pre_rows = 64;
+    int max_items = 0, max_pre_items = 0, max_v_tiles = 0, pre_rows = 64;
     std::vector<LayerBuffers> layers;
     bool borrowed_weights = false;  // the layer buffers belong to another stage (gllm_stage_share_weights)
     float* rope_cs = nullptr;  // device [max_position][d/2][2]
@@ -255,6 +255,7 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
     s->max_items = 4 * c.max_seqs + 1024;
     s->pre_rows = prefill_item_rows(c.n_q_heads, c.n_kv_heads);
     s->max_pre_items = c.max_tokens / s->pre_rows + c.max_seqs + 1;
+    s->max_v_tiles = c.max_tokens / kPage + 2 * c.max_seqs + 1;
     s->layers.resize(c.num_layers);
 
     auto bail = [&](hipError_t err, const char* what) {
@@ -284,11 +285,13 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
         auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
         m.tok_pos = take((size_t)c.max_tokens * 4);
         m.tok_page = take((size_t)c.max_tokens * 4);
+        m.tok_own_v = take((size_t)c.max_tokens * 4);
         m.bt_flat = take((size_t)c.max_seqs * c.max_blocks_per_seq * 4);
         m.dec_items = take((size_t)s->max_items * sizeof(DecodeItem));
         m.dec_order = take((size_t)s->max_items * 4);
         m.dec_rows = take((size_t)c.max_seqs * sizeof(DecodeRow));
         m.pre_items = take((size_t)s->max_pre_items * sizeof(PrefillItem));
+        m.v_tiles = take((size_t)s->max_v_tiles * sizeof(VTile));
         m.total = off;
         if ((e = hipMalloc((void**)&s->meta_dev, m.total)) != hipSuccess) return bail(e, "hipMalloc(metadata)");
         for (int i = 0; i < kStagingSlots; ++i) {
@@ -520,12 +523,15 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     if (s->staging_used[slot]) HIP_TRY(s, hipEventSynchronize(s->staging_ev[slot]));
     unsigned char* st_base = s->staging[slot];
     // compact layout for this batch: only what is used travels to the device
-    int64_t cnt_items = 0, cnt_pre = 0;
+    int64_t cnt_items = 0, cnt_pre = 0, cnt_vt = 0;
     for (int i = 0; i < S; ++i) {
         if (b->new_tokens[i] == 1) cnt_items += ceil_div((int64_t)b->cached_len[i] + 1, part);
-        else cnt_pre += ceil_div(b->new_tokens[i], s->pre_rows);
+        else {
+            cnt_pre += ceil_div(b->new_tokens[i], s->pre_rows);
+            cnt_vt += ((int64_t)b->cached_len[i] + b->new_tokens[i] - 1) / kPage - b->cached_len[i] / kPage + 1;
+        }
     }
-    if (cnt_items > s->max_items || cnt_pre > s->max_pre_items)
+    if (cnt_items > s->max_items || cnt_pre > s->max_pre_items || cnt_vt > s->max_v_tiles)
         return fail(s, GLLM_E_CAPACITY, "internal work list overflow");
     MetaLayout ml{};
     {
@@ -533,21 +539,25 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
         ml.tok_pos = take((size_t)T * 4);
         ml.tok_page = take((size_t)T * 4);
+        ml.tok_own_v = take((size_t)T * 4);
         ml.bt_flat = take((size_t)total_pages * 4);
         ml.dec_items = take((size_t)cnt_items * sizeof(DecodeItem));
         ml.dec_order = take((size_t)cnt_items * 4);
         ml.dec_rows = take((size_t)n_dec * sizeof(DecodeRow));
         ml.pre_items = take((size_t)cnt_pre * sizeof(PrefillItem));
+        ml.v_tiles = take((size_t)cnt_vt * sizeof(VTile));
         ml.total = off;
     }
     int32_t* tok_pos = (int32_t*)(st_base + ml.tok_pos);
     int32_t* tok_page = (int32_t*)(st_base + ml.tok_page);
+    int32_t* tok_own_v = (int32_t*)(st_base + ml.tok_own_v);
+    VTile* v_tiles = (VTile*)(st_base + ml.v_tiles);
     int32_t* bt_flat = (int32_t*)(st_base + ml.bt_flat);
     DecodeItem* dec_items = (DecodeItem*)(st_base + ml.dec_items);
     int32_t* dec_order = (int32_t*)(st_base + ml.dec_order);
     DecodeRow* dec_rows = (DecodeRow*)(st_base + ml.dec_rows);
     PrefillItem* pre_items = (PrefillItem*)(st_base + ml.pre_items);
-    int n_items = 0, n_rows = 0, n_pre = 0;
+    int n_items = 0, n_rows = 0, n_pre = 0, n_vt = 0;
     int64_t bt_off = 0, row = 0;
     for (int i = 0; i < S; ++i) {
         const int n = b->new_tokens[i], cl = b->cached_len[i];
@@ -557,7 +567,14 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         for (int t = 0; t < n; ++t) {
             tok_pos[row + t] = cl + t;
             tok_page[row + t] = tab[(cl + t) / kPage];
+            tok_own_v[row + t] = n == 1;
         }
+        if (n > 1)  // the V of a chunk is written run by run: the tokens that share a page
+            for (int p0 = cl; p0 < cl + n;) {
+                const int p1 = std::min(cl + n, (p0 / kPage + 1) * kPage);
+                v_tiles[n_vt++] = VTile{(int32_t)(row + p0 - cl), p1 - p0, tab[p0 / kPage], p0 % kPage};
+                p0 = p1;
+            }
         if (n == 1) {
             const int len = cl + 1;
             // equal shares (whole 32-key blocks) rather than full partitions plus a short remainder
@@ -593,6 +610,8 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
 
     const int32_t* d_tok_pos = (const int32_t*)(s->meta_dev + ml.tok_pos);
     const int32_t* d_tok_page = (const int32_t*)(s->meta_dev + ml.tok_page);
+    const int32_t* d_tok_own_v = (const int32_t*)(s->meta_dev + ml.tok_own_v);
+    const VTile* d_v_tiles = (const VTile*)(s->meta_dev + ml.v_tiles);
     const int32_t* d_bt = (const int32_t*)(s->meta_dev + ml.bt_flat);
     const DecodeItem* d_items = (const DecodeItem*)(s->meta_dev + ml.dec_items);
     const int32_t* d_order = (const int32_t*)(s->meta_dev + ml.dec_order);
@@ -631,6 +650,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
             a.q_out = s->q; a.ld_q = s->q_dim;
             a.k_pool = s->k_pool + (int64_t)l * pool_layer; a.v_pool = s->v_pool + (int64_t)l * pool_layer;
             a.T = Ti; a.n_q = c.n_q_heads; a.n_kv = c.n_kv_heads; a.d = d;
+            a.v_tiles = d_v_tiles; a.n_vtiles = n_vt; a.tok_own_v = d_tok_own_v;
             HIP_TRY(s, launch_rope_kv_write(a, st));
         }
         AttnArgs aa{};

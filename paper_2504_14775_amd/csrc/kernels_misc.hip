@@ -119,6 +119,46 @@ __global__ __launch_bounds__(256) void pack_gate_up_kernel(const bf16_t* __restr
         *reinterpret_cast<const u32x4*>(up + (int64_t)r * hidden + g * 8);
 }
 
+// V of one head of one run of tokens inside a page (see VTile): the page keeps the 16 slots of one head dimension contiguous
+// (32 bytes), so a thread gathers one dimension of up to 8 consecutive tokens -- neighbouring lanes read
+// neighbouring columns of the same rows -- and stores them as one 16-byte piece; neighbouring lanes store
+// neighbouring pieces.  Pieces that the run covers only in part are stored slot by slot.  The value of an
+// element is formed exactly as in the token workgroups (planes in order, then the bias).
+__device__ __forceinline__ void write_v_tile(const RopeKvArgs& a, const VTile vt, int hd) {
+    const int v_col0 = (a.n_q + a.n_kv) * a.d;
+    const int pieces = a.d * 2;  // (dim, half of the slots) of head hd
+    for (int pc = threadIdx.x; pc < pieces; pc += 256) {
+        const int hf = pc & 1, e = pc >> 1, he = hd * a.d + e;
+        const int s_lo = max(vt.slot0, hf * 8), s_hi = min(vt.slot0 + vt.n, hf * 8 + 8);  // slots of this piece in the run
+        if (s_lo >= s_hi) continue;
+        const int col = v_col0 + he;
+        const int64_t row_of_slot0 = (int64_t)vt.row0 - vt.slot0;  // row of slot s is row_of_slot0 + s (used for s_lo <= s < s_hi only)
+        const float b = a.bias ? (float)a.bias[col] : 0.f;
+        f32x8 val;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int sl = hf * 8 + k;
+            val[k] = 0.f;
+            if (sl >= s_lo && sl < s_hi) {
+                const float* src = a.qkv + (row_of_slot0 + sl) * a.ld_qkv + col;
+                float v = src[0];
+                for (int p = 1; p < a.planes; ++p) v += src[p * a.plane_stride];
+                if (a.bias) v += b;
+                val[k] = v;
+            }
+        }
+        const bf16x8 o = __builtin_convertvector(val, bf16x8);
+        bf16_t* vb = a.v_pool + ((int64_t)vt.page * a.n_kv + hd) * (int64_t)(a.d * kPage) + e * kPage + hf * 8;
+        if (s_hi - s_lo == 8) {
+            *reinterpret_cast<bf16x8*>(vb) = o;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (hf * 8 + k >= s_lo && hf * 8 + k < s_hi) vb[k] = o[k];
+        }
+    }
+}
+
 // One workgroup per token row.  q heads and k heads are rotated (rotate-half pairing: element j
 // pairs with j + d/2, angle pos * theta^(-2j/d) taken from the table); k and v are rounded to
 // bf16 and stored at (page, slot = pos % 16) in the layer's pool:
@@ -128,7 +168,12 @@ __global__ __launch_bounds__(256) void pack_gate_up_kernel(const bf16_t* __restr
 // takes it from the arguments.
 template <int PLANES>
 __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
-    const int t = blockIdx.x;
+    const int v_wgs = a.n_vtiles * a.n_kv;  // the first workgroups write the V runs, one (run, head) each
+    if ((int)blockIdx.x < v_wgs) {
+        write_v_tile(a, a.v_tiles[blockIdx.x / a.n_kv], blockIdx.x % a.n_kv);
+        return;
+    }
+    const int t = blockIdx.x - v_wgs;
     const int d = a.d, half = d / 2, hq = half / 4;  // a thread handles 4 consecutive pairs
     const int pos = a.tok_pos[t];
     const int64_t page = a.tok_page[t];
@@ -177,6 +222,7 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
             *reinterpret_cast<bf16x4*>(kb + (e1 >> 3) * (kPage * 8) + slot * 8 + (e1 & 7)) = bhi;
         }
     }
+    if (a.tok_own_v && !a.tok_own_v[t]) return;  // wave-uniform: a V run covers this token
     const int v_quads = a.n_kv * d / 4;
     for (int i = threadIdx.x; i < v_quads; i += 256) {
         const int hd = (i * 4) / d, e = (i * 4) % d;
@@ -184,6 +230,84 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(RopeKvArgs a) {
         bf16_t* vb = a.v_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage) + e * kPage + slot;
 #pragma unroll
         for (int u = 0; u < 4; ++u) vb[u * kPage] = v[u];
+    }
+}
+
+// The same for a single plane (the many-row case, where this kernel's time matters), with a token's work cut into
+// units of four columns -- rotated (lo, hi) quads of the q and k heads first, then v quads -- and unit
+// threadIdx.x + 256 * it handled in pass `it`: all loads of all ITERS passes are issued before the first result
+// is computed, so a workgroup waits for memory once instead of once per pass.
+template <int ITERS>
+__global__ __launch_bounds__(256) void rope_kv_write_batched_kernel(RopeKvArgs a) {
+    const int v_wgs = a.n_vtiles * a.n_kv;
+    if ((int)blockIdx.x < v_wgs) {
+        write_v_tile(a, a.v_tiles[blockIdx.x / a.n_kv], blockIdx.x % a.n_kv);
+        return;
+    }
+    const int t = blockIdx.x - v_wgs;
+    const int d = a.d, half = d / 2, hq = half / 4;
+    const int pos = a.tok_pos[t];
+    const int64_t page = a.tok_page[t];
+    const int slot = pos & (kPage - 1);
+    const float* row = a.qkv + (int64_t)t * a.ld_qkv;
+    const f32x4* cs = reinterpret_cast<const f32x4*>(a.rope_cs + (int64_t)pos * half * 2);
+    const bool own_v = !a.tok_own_v || a.tok_own_v[t];
+    const int q_quads = a.n_q * hq, rope_units = (a.n_q + a.n_kv) * hq, units = rope_units + (own_v ? a.n_kv * d / 4 : 0);
+    const int k_col0 = a.n_q * d, v_col0 = k_col0 + a.n_kv * d;
+    f32x4 lo[ITERS], hi[ITERS], c01[ITERS], c23[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int i = threadIdx.x + it * 256;
+        if (i < rope_units) {
+            const int ii = i < q_quads ? i : i - q_quads;
+            const int j = (ii % hq) * 4;
+            const int col = (i < q_quads ? 0 : k_col0) + (ii / hq) * d + j;
+            lo[it] = *reinterpret_cast<const f32x4*>(row + col);
+            hi[it] = *reinterpret_cast<const f32x4*>(row + col + half);
+            c01[it] = cs[j / 2];
+            c23[it] = cs[j / 2 + 1];
+            if (a.bias) {
+                lo[it] += __builtin_convertvector(*reinterpret_cast<const bf16x4*>(a.bias + col), f32x4);
+                hi[it] += __builtin_convertvector(*reinterpret_cast<const bf16x4*>(a.bias + col + half), f32x4);
+            }
+        } else if (i < units) {
+            const int col = v_col0 + (i - rope_units) * 4;
+            lo[it] = *reinterpret_cast<const f32x4*>(row + col);
+            if (a.bias) lo[it] += __builtin_convertvector(*reinterpret_cast<const bf16x4*>(a.bias + col), f32x4);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int i = threadIdx.x + it * 256;
+        if (i < rope_units) {
+            const bool is_q = i < q_quads;
+            const int ii = is_q ? i : i - q_quads;
+            const int hd = ii / hq, j = (ii % hq) * 4;
+            const f32x4 co = {c01[it][0], c01[it][2], c23[it][0], c23[it][2]}, si = {c01[it][1], c01[it][3], c23[it][1], c23[it][3]};
+            f32x4 rlo, rhi;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                rlo[v] = lo[it][v] * co[v] - hi[it][v] * si[v];
+                rhi[v] = hi[it][v] * co[v] + lo[it][v] * si[v];
+            }
+            const bf16x4 blo = __builtin_convertvector(rlo, bf16x4), bhi = __builtin_convertvector(rhi, bf16x4);
+            if (is_q) {
+                bf16_t* q = a.q_out + (int64_t)t * a.ld_q + hd * d;
+                *reinterpret_cast<bf16x4*>(q + j) = blo;
+                *reinterpret_cast<bf16x4*>(q + j + half) = bhi;
+            } else {
+                bf16_t* kb = a.k_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage);
+                const int e0 = j, e1 = j + half;
+                *reinterpret_cast<bf16x4*>(kb + (e0 >> 3) * (kPage * 8) + slot * 8 + (e0 & 7)) = blo;
+                *reinterpret_cast<bf16x4*>(kb + (e1 >> 3) * (kPage * 8) + slot * 8 + (e1 & 7)) = bhi;
+            }
+        } else if (i < units) {
+            const int e4 = (i - rope_units) * 4, hd = e4 / d, e = e4 % d;
+            const bf16x4 v = __builtin_convertvector(lo[it], bf16x4);
+            bf16_t* vb = a.v_pool + (page * a.n_kv + hd) * (int64_t)(d * kPage) + e * kPage + slot;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vb[u * kPage] = v[u];
+        }
     }
 }
 
@@ -253,12 +377,28 @@ hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, 
 
 hipError_t launch_rope_kv_write(const RopeKvArgs& a, hipStream_t stream) {
     if (a.T <= 0) return hipSuccess;
+    if (a.n_vtiles < 0 || (a.n_vtiles > 0 && (!a.v_tiles || !a.tok_own_v))) return hipErrorInvalidValue;
+    const int grid = a.T + a.n_vtiles * a.n_kv;
+    const int units = ((a.n_q + a.n_kv) * (a.d / 8) + a.n_kv * a.d / 4 + 255) / 256;  // passes of 256 four-column units
+    if (a.planes == 1 && units <= 8) {
+        switch (units) {
+            case 1: rope_kv_write_batched_kernel<1><<<grid, 256, 0, stream>>>(a); break;
+            case 2: rope_kv_write_batched_kernel<2><<<grid, 256, 0, stream>>>(a); break;
+            case 3: rope_kv_write_batched_kernel<3><<<grid, 256, 0, stream>>>(a); break;
+            case 4: rope_kv_write_batched_kernel<4><<<grid, 256, 0, stream>>>(a); break;
+            case 5: rope_kv_write_batched_kernel<5><<<grid, 256, 0, stream>>>(a); break;
+            case 6: rope_kv_write_batched_kernel<6><<<grid, 256, 0, stream>>>(a); break;
+            case 7: rope_kv_write_batched_kernel<7><<<grid, 256, 0, stream>>>(a); break;
+            default: rope_kv_write_batched_kernel<8><<<grid, 256, 0, stream>>>(a); break;
+        }
+        return hipGetLastError();
+    }
     switch (a.planes) {
-        case 1: rope_kv_write_kernel<1><<<a.T, 256, 0, stream>>>(a); break;
-        case 2: rope_kv_write_kernel<2><<<a.T, 256, 0, stream>>>(a); break;
-        case 4: rope_kv_write_kernel<4><<<a.T, 256, 0, stream>>>(a); break;
-        case 8: rope_kv_write_kernel<8><<<a.T, 256, 0, stream>>>(a); break;
-        default: rope_kv_write_kernel<-1><<<a.T, 256, 0, stream>>>(a); break;
+        case 1: rope_kv_write_kernel<1><<<grid, 256, 0, stream>>>(a); break;
+        case 2: rope_kv_write_kernel<2><<<grid, 256, 0, stream>>>(a); break;
+        case 4: rope_kv_write_kernel<4><<<grid, 256, 0, stream>>>(a); break;
+        case 8: rope_kv_write_kernel<8><<<grid, 256, 0, stream>>>(a); break;
+        default: rope_kv_write_kernel<-1><<<grid, 256, 0, stream>>>(a); break;
     }
     return hipGetLastError();
 }
