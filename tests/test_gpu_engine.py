@@ -111,3 +111,18 @@ def test_engine_generates_what_the_oracles_confirm(pages, depth, caching, sample
     print(f"[engine] {worst['batches']} micro-batches, hidden err {worst['h']:.3g}, logits err {worst['l']:.3g}, "
           f"{st['preemptions']} preemptions, {st['prefix_hit_tokens']} prefix-hit tokens", flush=True)
     eng.close()
+
+
+def test_streams_picked_for_the_lanes_are_distinct_and_usable():
+    print("stream calibration", flush=True)
+    cur = torch.cuda.current_stream()
+    for n, beside in ((0, ()), (1, (cur,)), (3, ())):
+        got = E.independent_streams(n, DEV, beside=beside)
+        assert len(got) == n and len({s.cuda_stream for s in got}) == n
+        assert all(s.cuda_stream != cur.cuda_stream for s in got)
+        x = torch.zeros(8, device=DEV)
+        for s in got:
+            with torch.cuda.stream(s):
+                x += 1                                      # (serialised below: one stream at a time)
+            s.synchronize()
+        assert float(x[0]) == n
