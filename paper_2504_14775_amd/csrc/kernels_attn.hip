@@ -63,9 +63,22 @@ struct AttnState {
 
 // Masks the V fragments of keys >= valid_end (slots that hold no data yet may contain any bit pattern,
 // also NaN, and 0 * NaN would poison the P.V product).  v[b] holds 4 keys of page 0 and 4 of page 1, dims block b.
-template <int D>
+// CONTIG: v[b] holds the 8 consecutive keys tb + 8G .. tb + 8G + 7 instead (see score_group).
+template <int D, bool CONTIG = false>
 __device__ __forceinline__ void mask_unwritten_v(u32x4 (&v)[D / 16], int tb, int valid_end, int lane) {
     const int G = lane >> 4;
+    if constexpr (CONTIG) {
+        int nv = valid_end - (tb + G * 8);
+        nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
+        uint32_t m[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m[w] = nv >= 2 * w + 2 ? 0xFFFFFFFFu : (nv == 2 * w + 1 ? 0x0000FFFFu : 0u);
+#pragma unroll
+        for (int b = 0; b < D / 16; ++b)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) v[b][w] &= m[w];
+        return;
+    }
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         int nv = valid_end - (tb + p * 16 + G * 4);
@@ -85,7 +98,10 @@ __device__ __forceinline__ void mask_unwritten_v(u32x4 (&v)[D / 16], int tb, int
 // Phase 1: raw scores q.k of this lane's 8 keys (not yet scaled), masked keys set to a huge negative.
 //   limit     : last key visible to this lane's column (causal / partition limit)
 //   need_mask : wave-uniform, false when the whole block is visible to every column of the group
-template <int D>
+// CONTIG: the caller has loaded the K fragments with their rows permuted (row i of fragment t = key
+// tb + 16 (i >> 3) + 8 ((i >> 2) & 1) + 4 t + (i & 3)), so that this lane's 8 scores are the 8 consecutive keys
+// tb + 8G .. tb + 8G + 7 (fragment 0 gives the first four, fragment 1 the last four).
+template <int D, bool CONTIG = false>
 __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2][D / 32], const bf16x8 (&qf)[D / 32],
                                             int tb, int limit, bool need_mask, int lane) {
     const int G = lane >> 4;
@@ -101,11 +117,18 @@ __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2]
         sc[4 + v] = s1[v];
     }
     if (need_mask) {
-        const int t0 = tb + G * 4;
+        if constexpr (CONTIG) {
+            const int t0 = tb + G * 8;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            if (t0 + v > limit) sc[v] = kNegBig;
-            if (t0 + 16 + v > limit) sc[4 + v] = kNegBig;
+            for (int v = 0; v < 8; ++v)
+                if (t0 + v > limit) sc[v] = kNegBig;
+        } else {
+            const int t0 = tb + G * 4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (t0 + v > limit) sc[v] = kNegBig;
+                if (t0 + 16 + v > limit) sc[4 + v] = kNegBig;
+            }
         }
     }
 }
@@ -375,16 +398,15 @@ __global__ void decode_combine_kernel(AttnArgs a, const DecodeRow* __restrict__ 
     *reinterpret_cast<bf16x4*>(a.out + (int64_t)rw.row * a.ld_o + hq * D + e) = __builtin_convertvector(acc, bf16x4);
 }
 
-// Two 8-byte LDS reads at addr + 512*B and addr + 512*(B + GAP) into one 4-register tuple (ds_read2st64_b64).
-// Written as assembly because the compiler pairs neighbouring dims blocks instead and then needs 3 register
-// moves per operand to regroup them.  The result is valid only after await_lds().
-template <int B, int GAP>
+// One 16-byte LDS read at addr + 512*B (dims block B of a V page).  Written as assembly so that the reads can be
+// issued early and awaited late: the result is valid only after await_lds().
+template <int B>
 __device__ __forceinline__ void read_v_operand(u32x4& v, uint32_t addr) {
-    asm volatile("ds_read2st64_b64 %0, %1 offset0:%2 offset1:%3" : "=v"(v) : "v"(addr), "n"(B), "n"(B + GAP) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(B * 512) : "memory");
 }
-template <int GAP, int N, int... Bs>
+template <int N, int... Bs>
 __device__ __forceinline__ void read_v_operands(u32x4 (&v)[N], uint32_t addr, std::integer_sequence<int, Bs...>) {
-    (read_v_operand<Bs, GAP>(v[Bs], addr), ...);
+    (read_v_operand<Bs>(v[Bs], addr), ...);
 }
 // Waits for all outstanding LDS reads; the registers are passed through the statement so that no use of them
 // can be scheduled before it.
@@ -400,11 +422,12 @@ __device__ __forceinline__ void await_lds(u32x4 (&v)[N]) {
 // Prefill: one workgroup of 4 waves per (item, group of HW query heads of one KV head).  An item is up
 // to 128/HW consecutive query rows of a chunk, so the workgroup owns 8 column groups of 16 (2 per wave)
 // that all share the same K/V: every 32-key block is brought into LDS once (global_load_lds into a ring
-// of 4 stages, three blocks in flight while one is processed: a block is only ~0.5 us of work, far less
+// of 3 stages, two blocks in flight while one is processed: a block is only ~0.5 us of work, far less
 // than the memory latency) and read by all 4 waves.
-// LDS holds the K pages exactly as the pool does and the V pages with a bank swizzle (see issue_block), so the
-// fragment reads are the same patterns as in the decode kernel.  Column group cb = 2*wave + c covers head (cb % HW) and query rows
-// 16*(cb / HW) .. +15 of the item.
+// Unlike the decode kernel, a lane here owns 8 consecutive keys of the block (the K operand rows are permuted
+// accordingly, see score_group), so a V operand is one 16-byte LDS read of 8 slots of one page; LDS holds the
+// pages as the pool does, except that the second K page is shifted by four slots (see issue_block).
+// Column group cb = 2*wave + c covers head (cb % HW) and query rows 16*(cb / HW) .. +15 of the item.
 // ------------------------------------------------------------------------------------------
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -445,10 +468,14 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a, c
     const bf16_t* pool = (wave < 2) ? a.k_pool : a.v_pool;
     auto page_id = [&](int blk) -> int { return bt[min(blk * 2 + (wave & 1), last_page)]; };
     auto issue_block = [&](int64_t page, int stage) {
-        // K pages are copied as they are.  V pages ([dim][16 slots], 32 bytes per dim) swap the two 16-byte halves
-        // of the dims whose bit 3 is set: the 16 dims that 16 lanes read together then sit in 16 different bank
-        // groups (as stored, dims d and d+8 would collide).  A lane picks the source piece for its LDS position.
-        const int src_lane = (wave < 2) ? lane : lane ^ ((lane >> 4) & 1);
+        // K page 0 and the V pages are copied as they are, K page 1 with slot s at the place of slot s ^ 4.  A 16-byte
+        // LDS read is served 16 lanes at a time -- measured: lanes 0-7 together with lanes 24-31, 8-15 with 16-23,
+        // and likewise in the upper half of the wave -- and is free of bank conflicts when those 16 lanes hit 16
+        // different 16-byte columns of the 256-byte bank line.  The K operand rows of such a group are slots
+        // {0-3, 8-11} (or {4-7, 12-15}) of page 0 and of page 1: the shift by four slots separates the two pages.
+        // The V operand of such a group is one half (16 bytes) of dims 0-7 and the other half of dims 8-15 of a
+        // 16-dim block: 16 different columns as stored.  A lane picks the source piece for its LDS position.
+        const int src_lane = wave == 1 ? lane ^ 4 : lane;
         const char* src = reinterpret_cast<const char*>(pool + (page * a.n_kv + kvh) * (int64_t)(D * kPage)) + src_lane * 16;
 #pragma unroll
         for (int i = 0; i < IPB; ++i)
@@ -461,29 +488,30 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a, c
         constexpr bool MASKED = decltype(masked)::value;
         float sc[NB][8];
         {
+            // fragment t, row r of the operand = slot 8 ((r >> 2) & 1) + 4 t + (r & 3) of page r >> 3 (see score_group)
             u32x4 kf[2][D / 32];
+            const int kpage = r >> 3, kslot = ((r >> 2) & 1) * 8 + (r & 3);
 #pragma unroll
-            for (int p = 0; p < 2; ++p)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int s = 0; s < D / 32; ++s)
-                    kf[p][s] = *reinterpret_cast<const u32x4*>(&lds[stage][p][(s * 64 + lane) * 16]);
+                    kf[t][s] = *reinterpret_cast<const u32x4*>(
+                        &lds[stage][kpage][((s * 4 + G) * 16 + ((kslot + 4 * t) ^ (4 * kpage))) * 16]);
 #pragma unroll
-            for (int c = 0; c < NB; ++c) score_group<D>(sc[c], kf, qf[c], tb, limit[c], MASKED, lane);
+            for (int c = 0; c < NB; ++c) score_group<D, true>(sc[c], kf, qf[c], tb, limit[c], MASKED, lane);
         }
-        // V^T operands: dims block b needs 4 keys of page 0 and 4 keys of page 1 in one 4-register operand.  One
-        // two-address LDS read (addresses PAGE_BYTES apart) delivers exactly that; the reads are issued before the
-        // exponentials and awaited after them.
+        // V^T operands: dims block b needs this lane's 8 consecutive keys of one dim: the 16 bytes of slots 0-7 or
+        // 8-15 of page G >> 1.  The reads are issued before the exponentials and awaited after them.
         u32x4 vf[D / 16];
         update_groups<D, NB, true>(
             st, sc, a.scale_log2,
             [&]() {
-                const uint32_t addr = (uint32_t)(uintptr_t)(
-                    &lds[stage][2][r * 32 + (((G >> 1) ^ ((r >> 3) & 1)) * 16) + (G & 1) * 8]);
-                read_v_operands<PAGE_BYTES / 512>(vf, addr, std::make_integer_sequence<int, D / 16>{});
+                const uint32_t addr = (uint32_t)(uintptr_t)(&lds[stage][2 + (G >> 1)][r * 32 + (G & 1) * 16]);
+                read_v_operands(vf, addr, std::make_integer_sequence<int, D / 16>{});
             },
             [&]() -> const u32x4 (&)[D / 16] {
                 await_lds(vf);
-                if (MASKED) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
+                if (MASKED) mask_unwritten_v<D, true>(vf, tb, last_pos + 1, lane);
                 return vf;
             });
     };
