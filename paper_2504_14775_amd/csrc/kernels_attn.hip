@@ -4,16 +4,16 @@
 // of 16 "columns" (for a decode row: the query heads that share a KV head; for a prefill chunk:
 // 16 consecutive query rows of one head), in transposed form so that nothing has to be moved
 // between lanes:
-//     S^T[key][col]  = K[key][:] . Q[col][:]          two 16x16x32 MFMA chains (one per page)
+//     S^T[key][col]  = K[key][:] . Q[col][:]          two 16x16x32 MFMA chains (16 of the 32 keys each)
 //     O^T[dim][col] += V^T[dim][key] . P^T[key][col]  one 16x16x32 MFMA per 16 dims
 // A 16x16x32 MFMA takes, per lane (r = lane % 16, G = lane / 16), 8 consecutive k-values of row r
 // (A operand) or column r (B operand), k-slots 8G..8G+7, and returns for column r the rows
-// 4G..4G+3.  So after the two S^T tiles a lane holds, for its column, keys 4G..4G+3 of page 0 and
-// of page 1 -- exactly the 8 k-slots it must supply as the B operand of the P.V product when those
-// 8 keys are assigned to k-slots 8G..8G+7.  The pool layouts make the matching A operands plain
-// coalesced loads:
-//   K page [d/8][16 slots][8]: k-step s of S^T reads the 1 KiB at (64 s + lane) * 16 bytes;
-//   V page [d][16 slots]:      dims 16b..16b+15 of P.V read 8 bytes at ((16b + r) * 16 + 4G) * 2.
+// 4G..4G+3.  The 32 keys are dealt to the rows of the two S^T tiles so that the 4 + 4 results a lane holds for
+// its column are the 8 consecutive keys 8G..8G+7 of the block (tile t, row i = slot 8((i>>2)&1) + 4t + (i&3) of
+// page i>>3) -- exactly the 8 k-slots it must supply as the B operand of the P.V product.  The pool layouts
+// make the matching A operands 16-byte pieces:
+//   K page [d/8][16 slots][8]: k-step s, tile t reads (group 4s + G, the slot above) of page r>>3;
+//   V page [d][16 slots]:      dims 16b..16b+15 of P.V read slots 8(G&1)..+7 of dim 16b + r of page G>>1.
 // Softmax is the running-reference form in base 2 (exponent s*log2(e)/sqrt(d) - m, see update_group);
 // all reductions follow logical key order, so the result does not depend on which physical pages
 // hold the keys.
@@ -26,10 +26,12 @@ namespace {
 
 constexpr float kNegBig = -1.0e30f;
 
+// K and V operands of one block of 32 keys (two pages) in the layout score_group expects: a lane owns the 8
+// consecutive keys 8G .. 8G+7 of the block.
 template <int D>
 struct KvFrag {
-    u32x4 k[2][D / 32];  // [page][k-step]
-    u32x4 v[D / 16];     // [16-dim block]: elements 0,1 = 4 keys of page 0, elements 2,3 = 4 keys of page 1
+    u32x4 k[2][D / 32];  // [fragment t][k-step]: operand row r = slot 8 ((r >> 2) & 1) + 4 t + (r & 3) of page r >> 3
+    u32x4 v[D / 16];     // [16-dim block]: slots 8 (G & 1) .. + 7 of dim r of page G >> 1
 };
 
 template <int D>
@@ -37,20 +39,15 @@ __device__ __forceinline__ void load_kv(KvFrag<D>& f, const bf16_t* __restrict__
                                         int64_t page0, int64_t page1, int n_kv, int kvh, int lane) {
     constexpr int64_t PH = (int64_t)D * kPage;  // elements of one (page, head)
     const int r = lane & 15, G = lane >> 4;
-    const int64_t pg[2] = {page0, page1};
+    // K page layout [d/8 groups][16 slots][8]: 16 bytes per (group, slot); V page layout [d][16 slots]
+    const bf16_t* kb = kp + (((r >> 3) ? page1 : page0) * n_kv + kvh) * PH + (G * kPage + ((r >> 2) & 1) * 8 + (r & 3)) * 8;
+    const bf16_t* vb = vp + (((G >> 1) ? page1 : page0) * n_kv + kvh) * PH + r * kPage + (G & 1) * 8;
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const bf16_t* kb = kp + (pg[p] * n_kv + kvh) * PH + lane * 8;
-        const bf16_t* vb = vp + (pg[p] * n_kv + kvh) * PH + r * kPage + G * 4;
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int s = 0; s < D / 32; ++s) f.k[p][s] = *reinterpret_cast<const u32x4*>(kb + s * 512);
+        for (int s = 0; s < D / 32; ++s) f.k[t][s] = *reinterpret_cast<const u32x4*>(kb + s * 512 + t * 32);
 #pragma unroll
-        for (int b = 0; b < D / 16; ++b) {
-            const u32x2 t = *reinterpret_cast<const u32x2*>(vb + b * 256);
-            f.v[b][2 * p] = t[0];
-            f.v[b][2 * p + 1] = t[1];
-        }
-    }
+    for (int b = 0; b < D / 16; ++b) f.v[b] = *reinterpret_cast<const u32x4*>(vb + b * 256);
 }
 
 // State of NB column groups across the key loop.
@@ -62,46 +59,32 @@ struct AttnState {
 };
 
 // Masks the V fragments of keys >= valid_end (slots that hold no data yet may contain any bit pattern,
-// also NaN, and 0 * NaN would poison the P.V product).  v[b] holds 4 keys of page 0 and 4 of page 1, dims block b.
-// CONTIG: v[b] holds the 8 consecutive keys tb + 8G .. tb + 8G + 7 instead (see score_group).
-template <int D, bool CONTIG = false>
+// also NaN, and 0 * NaN would poison the P.V product).  v[b] holds this lane's 8 keys tb + 8G .. tb + 8G + 7 of dims
+// block b, two per register.
+template <int D>
 __device__ __forceinline__ void mask_unwritten_v(u32x4 (&v)[D / 16], int tb, int valid_end, int lane) {
     const int G = lane >> 4;
-    if constexpr (CONTIG) {
-        int nv = valid_end - (tb + G * 8);
-        nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
-        uint32_t m[4];
+    int nv = valid_end - (tb + G * 8);
+    nv = nv < 0 ? 0 : (nv > 8 ? 8 : nv);
+    uint32_t m[4];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) m[w] = nv >= 2 * w + 2 ? 0xFFFFFFFFu : (nv == 2 * w + 1 ? 0x0000FFFFu : 0u);
+    for (int w = 0; w < 4; ++w) m[w] = nv >= 2 * w + 2 ? 0xFFFFFFFFu : (nv == 2 * w + 1 ? 0x0000FFFFu : 0u);
 #pragma unroll
-        for (int b = 0; b < D / 16; ++b)
+    for (int b = 0; b < D / 16; ++b)
 #pragma unroll
-            for (int w = 0; w < 4; ++w) v[b][w] &= m[w];
-        return;
-    }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        int nv = valid_end - (tb + p * 16 + G * 4);
-        nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
-        const uint32_t m0 = nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0x0000FFFFu : 0u);
-        const uint32_t m1 = nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0x0000FFFFu : 0u);
-#pragma unroll
-        for (int b = 0; b < D / 16; ++b) {
-            v[b][2 * p] &= m0;
-            v[b][2 * p + 1] &= m1;
-        }
-    }
+        for (int w = 0; w < 4; ++w) v[b][w] &= m[w];
 }
 
 // One column group against one block of 32 keys starting at key index tb, in two phases so that callers
 // can fetch the V fragments only after the K fragments are dead.
 // Phase 1: raw scores q.k of this lane's 8 keys (not yet scaled), masked keys set to a huge negative.
+// The rows of the two K operands are permuted -- row i of fragment t is key tb + 16 (i >> 3) + 8 ((i >> 2) & 1) +
+// 4 t + (i & 3) -- so that the accumulators of lane group G are the 8 consecutive keys tb + 8G .. tb + 8G + 7
+// (fragment 0 gives the first four, fragment 1 the last four): exactly the 8 k-values this lane supplies to the
+// P.V product, whose V operand is then 8 consecutive slots of one page (16 contiguous bytes).
 //   limit     : last key visible to this lane's column (causal / partition limit)
 //   need_mask : wave-uniform, false when the whole block is visible to every column of the group
-// CONTIG: the caller has loaded the K fragments with their rows permuted (row i of fragment t = key
-// tb + 16 (i >> 3) + 8 ((i >> 2) & 1) + 4 t + (i & 3)), so that this lane's 8 scores are the 8 consecutive keys
-// tb + 8G .. tb + 8G + 7 (fragment 0 gives the first four, fragment 1 the last four).
-template <int D, bool CONTIG = false>
+template <int D>
 __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2][D / 32], const bf16x8 (&qf)[D / 32],
                                             int tb, int limit, bool need_mask, int lane) {
     const int G = lane >> 4;
@@ -117,19 +100,10 @@ __device__ __forceinline__ void score_group(float (&sc)[8], const u32x4 (&kf)[2]
         sc[4 + v] = s1[v];
     }
     if (need_mask) {
-        if constexpr (CONTIG) {
-            const int t0 = tb + G * 8;
+        const int t0 = tb + G * 8;
 #pragma unroll
-            for (int v = 0; v < 8; ++v)
-                if (t0 + v > limit) sc[v] = kNegBig;
-        } else {
-            const int t0 = tb + G * 4;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (t0 + v > limit) sc[v] = kNegBig;
-                if (t0 + 16 + v > limit) sc[4 + v] = kNegBig;
-            }
-        }
+        for (int v = 0; v < 8; ++v)
+            if (t0 + v > limit) sc[v] = kNegBig;
     }
 }
 
@@ -424,9 +398,9 @@ __device__ __forceinline__ void await_lds(u32x4 (&v)[N]) {
 // that all share the same K/V: every 32-key block is brought into LDS once (global_load_lds into a ring
 // of 3 stages, two blocks in flight while one is processed: a block is only ~0.5 us of work, far less
 // than the memory latency) and read by all 4 waves.
-// Unlike the decode kernel, a lane here owns 8 consecutive keys of the block (the K operand rows are permuted
-// accordingly, see score_group), so a V operand is one 16-byte LDS read of 8 slots of one page; LDS holds the
-// pages as the pool does, except that the second K page is shifted by four slots (see issue_block).
+// A lane owns 8 consecutive keys of the block (the K operand rows are permuted accordingly, see score_group),
+// so a V operand is one 16-byte LDS read of 8 slots of one page; LDS holds the pages as the pool does, except
+// that the second K page is shifted by four slots (see issue_block).
 // Column group cb = 2*wave + c covers head (cb % HW) and query rows 16*(cb / HW) .. +15 of the item.
 // ------------------------------------------------------------------------------------------
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -498,7 +472,7 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a, c
                     kf[t][s] = *reinterpret_cast<const u32x4*>(
                         &lds[stage][kpage][((s * 4 + G) * 16 + ((kslot + 4 * t) ^ (4 * kpage))) * 16]);
 #pragma unroll
-            for (int c = 0; c < NB; ++c) score_group<D, true>(sc[c], kf, qf[c], tb, limit[c], MASKED, lane);
+            for (int c = 0; c < NB; ++c) score_group<D>(sc[c], kf, qf[c], tb, limit[c], MASKED, lane);
         }
         // V^T operands: dims block b needs this lane's 8 consecutive keys of one dim: the 16 bytes of slots 0-7 or
         // 8-15 of page G >> 1.  The reads are issued before the exponentials and awaited after them.
@@ -511,7 +485,7 @@ __global__ __launch_bounds__(256, 3) void prefill_attention_kernel(AttnArgs a, c
             },
             [&]() -> const u32x4 (&)[D / 16] {
                 await_lds(vf);
-                if (MASKED) mask_unwritten_v<D, true>(vf, tb, last_pos + 1, lane);
+                if (MASKED) mask_unwritten_v<D>(vf, tb, last_pos + 1, lane);
                 return vf;
             });
     };
