@@ -1,8 +1,6 @@
 """Shared test plumbing: synthetic inputs as host numpy arrays (bf16 as uint16 bits)."""
 from __future__ import annotations
 
-import dataclasses
-
 import numpy as np
 
 from paper_2504_14775_amd import synth
