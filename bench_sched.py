@@ -32,10 +32,10 @@ import numpy as np
 from paper_2504_14775_amd import sched as S
 
 # stage time model, ns: least-squares fit of bench_series.py (16 hybrid batches back to back on the 70B-shaped stage,
-# 20 layers on one MI355X; worst residual 8 %): 9.4 ms fixed (the 34 GB of weights stream once per batch whatever its
-# size), 28.9 us per new token (GEMMs and the row-wise kernels), 11.7 ns per cached token a decode row reads,
-# 0.87 ns per (query, key) pair of prefill attention
-MODEL = (9_400_000, 28_900, 12, 893)
+# 20 layers on one MI355X; worst residual 7 %): 8.9 ms fixed (the 34 GB of weights stream once per batch whatever its
+# size), 28.9 us per new token (GEMMs and the row-wise kernels), 11.8 ns per cached token a decode row reads,
+# 0.58 ns per (query, key) pair of prefill attention
+MODEL = (8_900_000, 28_900, 12, 593)
 
 
 def make_trace(n, rate_per_s, seed):
