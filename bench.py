@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+SETUP_PASSES = 8            # untimed passes before the warm-up: first-use costs of every kernel and staging slot
 
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by a
 # plain 1 GiB copy (profiles/stage_llama3_8b_pp4_hbm_traffic.txt): mean over the GEMM launches of a step,
@@ -132,7 +133,7 @@ def main():
 
     # first-use costs (code objects, every metadata staging slot, the clocks coming up from idle) are paid here, as
     # part of the set-up: with fewer than about eight passes before the timed region they add 10-20 ms to it
-    for _ in range(8):
+    for _ in range(SETUP_PASSES):
         step()
     torch.cuda.synchronize()
     for _ in range(args.warmup):
@@ -224,7 +225,7 @@ def main():
     line = {
         "metric": "stage tokens/sec on mixed prefill+decode batch",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "setup_passes": SETUP_PASSES, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.config + (f"[first {args.layers} layers]" if args.layers > 0 else ""), "layers": L, "tokens_per_batch": T,
                    "prefill_tokens": int(batch.new_tokens[batch.new_tokens > 1].sum()),
