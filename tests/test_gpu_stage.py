@@ -331,3 +331,36 @@ def test_two_stage_objects_over_one_set_of_weights():
     dk, dv = to_dev_bits(kp0), to_dev_bits(vp0)
     out, _ = owner.run(batch, dk, dv, x, want_f32=False)
     assert np.array_equal(bits_of(out), got[0][0])
+
+
+@pytest.mark.parametrize("hidden,planes", [(256, 1), (1024, 2)])
+def test_chunk_runs_at_every_page_alignment_write_exactly_their_slots(hidden, planes):
+    """Chunks whose tokens fall into pages in every way the V writer distinguishes: a run that ends a page, one that
+    starts one, whole pages, a run of one at either edge, a chunk inside a single page, next to decode rows.  The pool
+    starts as a sentinel pattern: exactly the slots of the new tokens change, and they hold the oracle's values.
+    (The hidden size decides whether the QKV projection is split along k: the single-plane writer and the general one.)"""
+    print(f"chunk runs vs page boundaries, hidden {hidden}: {planes} plane(s)", flush=True)
+    shape = synth.StageShape("runs", 1, hidden, 4, 2, 64, 384)
+    #        (new, cached): 15|16 split    one page    page+1      1+page+1     inside    decode rows
+    seqs = [(2, 15), (16, 16), (17, 32), (18, 15), (5, 3), (1, 15), (1, 16), (1, 0), (33, 0), (31, 17)]
+    batch = synth.build_batch(seqs, 21, spare_blocks=3)
+    assert B.gllm_op_gemm_plan(batch.num_tokens, 512, hidden, 0, 8)[1] == planes
+    w = layer_weights_np(shape, 21)
+    n_el = shape.num_layers * synth.pool_elems_per_layer(shape, batch.num_blocks)
+    kp0 = np.full(n_el, SENT, dtype=np.uint16)
+    vp0 = kp0.copy()
+    # the cached prefixes must hold real values: fill them with the generator's pool, keep the rest as sentinels
+    kg, vg = pool_np(shape, 21, batch.num_blocks)
+    cached = np.zeros((batch.num_blocks, 16), dtype=bool)
+    for s, (n, c) in enumerate(seqs):
+        pos = np.arange(c)
+        cached[batch.block_tables[s, pos // 16], pos % 16] = True
+    km = np.broadcast_to(cached[:, None, None, :, None], (batch.num_blocks, shape.n_kv_heads, shape.head_dim // 8, 16, 8)).reshape(-1)
+    vm = np.broadcast_to(cached[:, None, None, :], (batch.num_blocks, shape.n_kv_heads, shape.head_dim, 16)).reshape(-1)
+    kp0[km], vp0[vm] = kg[km], vg[vm]
+    r = run_both(shape, w, batch, kp0, vp0, hidden_np(shape, 21, batch.num_tokens))
+    assert_output("runs", r, literal=False)
+    mk, mv = written_mask(shape, batch)
+    n = check_pool("K", r["gk"], kp0, r["kp"], mask=mk)
+    check_pool("V", r["gv"], vp0, r["vp"], mask=mv)
+    assert n == batch.num_tokens * shape.n_kv_heads * shape.head_dim
