@@ -335,6 +335,11 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
         case 6: return launch_tile<128, 128, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
         case 7: return launch_tile<64, 128, 2, 2, MODE, 3>(GLLM_TILE_ARGS);
+        case 9:  // one 288-row tile covers all rows; it reads 288 of them, which the row padding (to 256) covers above 256
+            if constexpr (MODE != GEMM_SWIGLU_BF16) {
+                if (m <= 256 || m > 288) return hipErrorInvalidValue;
+                return launch_tile<288, 192, 3, 2, MODE>(GLLM_TILE_ARGS);
+            } else return hipErrorInvalidValue;
         case 5:
             if constexpr (MODE != GEMM_SWIGLU_BF16) return launch_tile<256, 192, 4, 2, MODE>(GLLM_TILE_ARGS);
             else return hipErrorInvalidValue;
@@ -419,6 +424,7 @@ int gemm_mixed_rem_cols(int m, int n) {
 // for few rows).  A partial last round of 256x256 tiles that covers at most half of the compute units can be
 // run with half-width tiles instead (mixed launch, ~0.55 of a round).  Split-K multiplies the number of tiles
 // and divides the k-steps, at the price of writing one fp32 plane per split (mostly hidden under other tiles).
+// For 257..288 rows a 288x192 tile (6 waves, wave tile 96x96) covers all rows in one band.
 // Up to 64 rows the product is a stream of the weights: a 64x128 tile with three LDS stages (two workgroups per
 // compute unit, 64 KiB of weights in flight on each, half the activation traffic of a 128-row tile) costs
 // 0.30 k_steps per tile, but not less than the weights take at 5.5 TB/s, plus 2; measured 20-35 % faster than
@@ -435,10 +441,11 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
         const bool skinny = m <= 64 && n % 128 == 0;
         if (g_rowmix_planned && gemm_rowmix_rem_rows(m, n) > 0) {
             // (evaluated first: on equal cost it is kept -- whole rounds hide that it always does less work)
-            // whole bands as 256x256 tiles; the last band's tiles cost 0.4 (64 rows) or 0.6 (128 rows) of one and go
-            // first into the compute units the last round of big tiles leaves idle
+            // whole bands as 256x256 tiles; the last band's tiles go first into the compute units the last round of
+            // big tiles leaves idle; those that do not fit there stream their weights from HBM once more and cost
+            // 0.8 (64 rows) or 0.9 (128 rows) of a big tile (measured on the 128256-column vocabulary projection)
             const int rr = gemm_rowmix_rem_rows(m, n);
-            const double frac = rr == 64 ? 0.4 : 0.6;
+            const double frac = rr == 64 ? 0.8 : 0.9;
             const int64_t big = (int64_t)(m / 256) * (n / 256) * s, small = (int64_t)(n / 256) * s;
             const int64_t rem_big = big % 256;
             const int64_t room = rem_big > 0 ? (256 - rem_big) * (rr == 64 ? 2 : 1) : 0;
@@ -458,6 +465,14 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
             const int64_t tiles = ceil_div(m, 256) * (int64_t)(n / 192) * s;
             const double cost = (double)ceil_div(tiles, 256) * (steps * 0.88 + 6.0) + plane_cost;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{5, s}; }
+        }
+        if (m > 256 && m <= 288 && n % 192 == 0 && mode != GEMM_SWIGLU_BF16) {
+            // 257..288 rows (a micro-batch of 256 decode rows plus the ends of a few chunks): one 288x192 tile per
+            // column block reads the weights once where every 256-row shape needs a second band; a k-step of it costs
+            // 1.07 of a 256x256 one when the weights stream from HBM
+            const int64_t tiles = (int64_t)(n / 192) * s;
+            const double cost = (double)ceil_div(tiles, 256) * (steps * 1.07 + 6.0) + plane_cost;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{9, s}; }
         }
         if (n % 128 == 0 && !skinny) {
             const int64_t tiles = ceil_div(m, 128) * (int64_t)(n / 128) * s;

@@ -63,7 +63,7 @@ def test_gemm_planner_choices_are_launchable():
     """Host logic of the tile / split-K planner: whatever it picks must satisfy the launch rules of that tile
     (column multiple, split divides the 64-wide k-steps, splits only in store mode), for the stage shapes and a
     sweep of ragged row counts."""
-    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128, 7: 128, 8: 256}
+    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128, 7: 128, 8: 256, 9: 192}
     seen = set()
     for shape in synth.SHAPES.values():
         H, I = shape.hidden, shape.intermediate
@@ -71,7 +71,7 @@ def test_gemm_planner_choices_are_launchable():
         n_qkv = pad((shape.n_q_heads + 2 * shape.n_kv_heads) * shape.head_dim, 256)
         problems = [(n_qkv, pad(H, 64), 0), (pad(H, 256), pad(shape.n_q_heads * shape.head_dim, 64), 0),
                     (2 * pad(I, 256), pad(H, 64), 2), (pad(H, 256), pad(I, 256), 0)]
-        for m in (1, 17, 128, 256, 257, 512, 1000, 2048, 2560, 4160):
+        for m in (1, 17, 128, 256, 257, 288, 289, 512, 1000, 2048, 2560, 4160):
             for n, k, mode in problems:
                 tile, splits = B.gllm_op_gemm_plan(m, n, k, mode, 8)
                 seen.add(tile)
@@ -83,11 +83,16 @@ def test_gemm_planner_choices_are_launchable():
                     assert m <= 64
                 if tile == 8:
                     assert m > 256 and 0 < m % 256 <= 128
+                if tile == 9:
+                    assert 256 < m <= 288 and mode == 0
                 if tile == 4:
                     tiles = ((m + 255) // 256) * (n // 256)
                     assert splits == 1 and tiles >= 256 and 0 < tiles % 256 <= 128
                 assert B.gllm_op_gemm_plan(m, n, k, mode, 8) == (tile, splits)          # deterministic
                 assert B.gllm_op_gemm_plan(m, n, k, mode, 1)[1] == 1                    # the cap is respected
     assert {3, 6, 7, 8}.issubset(seen)   # big problems get 256x256 tiles (with a short last band where rows are left over), few rows the deep 128x128 or the 64x128 one
+    # the vocabulary projection of a micro-batch of 256 decode rows plus one chunk end: one 288-row band
+    assert B.gllm_op_gemm_plan(257, 128256, 4096, 0, 1) == (9, 1)
+    assert B.gllm_op_gemm_plan(256, 128256, 4096, 0, 1)[0] == 3 and B.gllm_op_gemm_plan(289, 128256, 4096, 0, 1)[0] == 8
     with pytest.raises(B.GllmError):
         B.gllm_op_gemm_plan(128, 100, 4096, 0, 8)

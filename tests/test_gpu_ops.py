@@ -132,6 +132,31 @@ def test_gemm_row_mixed_launch(M):
     assert np.all(err <= np.abs(ref_s) * 2.0 ** -7 + 1e-4), float(err.max())
 
 
+@pytest.mark.parametrize("M", [257, 270, 288])
+def test_gemm_288_row_tile(M):
+    """All of 257..288 rows in one band of 288x192 tiles (six waves): store, add and split-K planes; refused outside
+    that row range, for other column counts and for SwiGLU."""
+    N, K = 576, 384
+    print(f"gemm 288x192 tile M={M}", flush=True)
+    a = rand_bits(10, 1, (M, K), 1.0)
+    w = rand_bits(10, 2, (N, K), 0.05)
+    ref = oracle.linear(oracle.bf16_to_f64(a), w)
+    da, dw = to_dev_bits(padded_rows(a, 512)), to_dev_bits(w)
+    out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, 9)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, 9)
+    planes = torch.full((2, M, N), 9.0, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16_splitk(da, dw, planes, M, N, K, 9, 2)
+    torch.cuda.synchronize()
+    scale = np.abs(ref).max()
+    assert np.abs(out.cpu().numpy().astype(np.float64) - 2 * ref).max() <= 4e-5 * scale + 1e-6
+    assert np.abs(planes.cpu().numpy().astype(np.float64).sum(axis=0) - ref).max() <= 2e-5 * scale + 1e-6
+    for m, n, mode in ((256, N, B.GEMM_STORE_F32), (289, N, B.GEMM_STORE_F32), (M, 512, B.GEMM_STORE_F32), (M, 768, B.GEMM_SWIGLU_BF16)):
+        with pytest.raises(B.GllmError) as e:
+            B.gllm_op_gemm_bf16(da, to_dev_bits(rand_bits(10, 3, (768, K), 0.05)), torch.empty(512, 768, device=DEV), m, n, K, mode, 9)
+        assert e.value.status == -7          # GLLM_E_UNSUPPORTED
+
+
 def test_gemm_row_mixed_launch_refuses_shapes_without_a_short_last_band():
     a = torch.zeros(1024, 128, dtype=torch.bfloat16, device=DEV)
     w = torch.zeros(256, 128, dtype=torch.bfloat16, device=DEV)
