@@ -79,6 +79,10 @@ constexpr int kSampleThreads = 1024;
 constexpr int kSampleWaves = kSampleThreads / 64;
 constexpr int kCompact = 1024;
 constexpr int kList = 4096;  // top-k candidates held in LDS while the k-th largest is selected among them
+// the short-list path gives every thread one list entry (sort, masses) and keeps the list in the reduction arrays;
+// the histogram is cleared by the first 256 threads; block_sums keeps up to 15 values per wave in those arrays
+static_assert(kCompact == kSampleThreads, "the short list has one entry per thread");
+static_assert(kSampleThreads >= 256 && 15 * kSampleWaves <= kSampleThreads, "reduction arrays too small");
 
 // order-preserving map from float to unsigned: a < b  <=>  key(a) < key(b) (for non-NaN values)
 __device__ __forceinline__ uint32_t float_key(float f) {
