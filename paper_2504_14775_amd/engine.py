@@ -60,6 +60,27 @@ class _Slot:
     num_tokens: int = 0
 
 
+def pick_independent(n: int, fixed: int, total: int, clash: Dict[Tuple[int, int], bool]) -> List[int]:
+    """Host logic of independent_streams: indices of n of the candidates fixed .. total-1 such that no two of them,
+    and none of them with one of the candidates 0 .. fixed-1, clash (clash[(i, j)], i < j).  Greedy from every starting
+    candidate, first complete set wins; when no complete set exists the largest one found is filled up with the lowest
+    remaining indices."""
+    best: List[int] = []
+    for first in range(fixed, total):
+        if any(clash[(q, first)] for q in range(fixed)):
+            continue
+        pick = list(range(fixed)) + [first]
+        for k in range(fixed, total):
+            if k not in pick and len(pick) < fixed + n and not any(clash[(min(k, q), max(k, q))] for q in pick):
+                pick.append(k)
+        if len(pick) - fixed > len(best):
+            best = pick[fixed:]
+        if len(best) >= n:
+            break
+    rest = [k for k in range(fixed, total) if k not in best]
+    return (best + rest)[:n]
+
+
 def independent_streams(n: int, device: str = "cuda", candidates: int = 8, beside: Sequence = ()) -> List:
     """n streams whose kernels can run at the same time.  The runtime multiplexes streams onto a few hardware
     queues (four per process here), fixed per stream when it is made, and two streams that share a queue run their
@@ -91,20 +112,7 @@ def independent_streams(n: int, device: str = "cuda", candidates: int = 8, besid
     run(cands[:1])                                             # first-use costs
     alone = min(run(cands[:1]) for _ in range(3))
     clash = {(i, j): run([cands[i], cands[j]]) > 1.5 * alone for i, j in itertools.combinations(range(len(cands)), 2)}
-    best: List[int] = []
-    for first in range(fixed, len(cands)):
-        pick = list(range(fixed)) + [first]
-        if any(clash[(q, first)] for q in range(fixed)):
-            continue
-        for k in range(fixed, len(cands)):
-            if k not in pick and len(pick) < fixed + n and not any(clash[(min(k, q), max(k, q))] for q in pick):
-                pick.append(k)
-        if len(pick) - fixed > len(best):
-            best = pick[fixed:]
-        if len(best) == n:
-            break
-    rest = [k for k in range(fixed, len(cands)) if k not in best]
-    return [cands[k] for k in (best + rest)[:n]]
+    return [cands[k] for k in pick_independent(n, fixed, len(cands), clash)]
 
 
 class Engine:
