@@ -150,7 +150,10 @@ gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);
  *   that is cut into equal shares of whole 32-key blocks, and the longest shares are launched first.
  *   "overlap_attention" (default 1): prefill attention of a layer runs on an internal side stream next to
  *   decode attention (forked from and joined back into the caller's stream with events); 0 keeps every
- *   kernel on the caller's stream.  Per-kernel profiling always uses the single-stream order.
+ *   kernel on the caller's stream.  Per-kernel profiling always uses the single-stream order.  (The runtime maps
+ *   streams onto a few hardware queues; when the side stream happens to share the caller's queue the two kernels
+ *   simply run one after the other.  Callers that run several stages on several streams of their own may do better
+ *   with 0: every further stream competes for those queues.)
  *   "gemm_row_mixed" (default 1; process-wide, not per stage): the GEMM planner may cover a last band of at most
  *   128 token rows with 64- or 128-row tiles instead of a whole band of 256 (tile 8 of gllm_op_gemm_bf16).
  * Unknown names give GLLM_E_INVALID. */
