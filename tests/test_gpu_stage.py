@@ -333,6 +333,24 @@ def test_two_stage_objects_over_one_set_of_weights():
     assert np.array_equal(bits_of(out), got[0][0])
 
 
+def sentinel_pool_with_prefixes(shape, batch, seed):
+    """A pool of sentinel bit patterns in which only the cached positions of the batch's sequences hold real values
+    (the generator's): what a forward pass may read is defined, everything it must not touch is recognisable."""
+    n_el = shape.num_layers * synth.pool_elems_per_layer(shape, batch.num_blocks)
+    kp0 = np.full(n_el, SENT, dtype=np.uint16)
+    vp0 = kp0.copy()
+    kg, vg = pool_np(shape, seed, batch.num_blocks)
+    cached = np.zeros((batch.num_blocks, 16), dtype=bool)
+    for s in range(batch.num_seqs):
+        pos = np.arange(int(batch.cached_len[s]))
+        cached[batch.block_tables[s, pos // 16], pos % 16] = True
+    L, nkv, d = shape.num_layers, shape.n_kv_heads, shape.head_dim
+    km = np.broadcast_to(cached[None, :, None, None, :, None], (L, batch.num_blocks, nkv, d // 8, 16, 8)).reshape(-1)
+    vm = np.broadcast_to(cached[None, :, None, None, :], (L, batch.num_blocks, nkv, d, 16)).reshape(-1)
+    kp0[km], vp0[vm] = kg[km], vg[vm]
+    return kp0, vp0
+
+
 @pytest.mark.parametrize("hidden,planes", [(256, 1), (1024, 2)])
 def test_chunk_runs_at_every_page_alignment_write_exactly_their_slots(hidden, planes):
     """Chunks whose tokens fall into pages in every way the V writer distinguishes: a run that ends a page, one that
@@ -346,21 +364,35 @@ def test_chunk_runs_at_every_page_alignment_write_exactly_their_slots(hidden, pl
     batch = synth.build_batch(seqs, 21, spare_blocks=3)
     assert B.gllm_op_gemm_plan(batch.num_tokens, 512, hidden, 0, 8)[1] == planes
     w = layer_weights_np(shape, 21)
-    n_el = shape.num_layers * synth.pool_elems_per_layer(shape, batch.num_blocks)
-    kp0 = np.full(n_el, SENT, dtype=np.uint16)
-    vp0 = kp0.copy()
-    # the cached prefixes must hold real values: fill them with the generator's pool, keep the rest as sentinels
-    kg, vg = pool_np(shape, 21, batch.num_blocks)
-    cached = np.zeros((batch.num_blocks, 16), dtype=bool)
-    for s, (n, c) in enumerate(seqs):
-        pos = np.arange(c)
-        cached[batch.block_tables[s, pos // 16], pos % 16] = True
-    km = np.broadcast_to(cached[:, None, None, :, None], (batch.num_blocks, shape.n_kv_heads, shape.head_dim // 8, 16, 8)).reshape(-1)
-    vm = np.broadcast_to(cached[:, None, None, :], (batch.num_blocks, shape.n_kv_heads, shape.head_dim, 16)).reshape(-1)
-    kp0[km], vp0[vm] = kg[km], vg[vm]
+    kp0, vp0 = sentinel_pool_with_prefixes(shape, batch, 21)
     r = run_both(shape, w, batch, kp0, vp0, hidden_np(shape, 21, batch.num_tokens))
     assert_output("runs", r, literal=False)
     mk, mv = written_mask(shape, batch)
     n = check_pool("K", r["gk"], kp0, r["kp"], mask=mk)
     check_pool("V", r["gv"], vp0, r["vp"], mask=mv)
     assert n == batch.num_tokens * shape.n_kv_heads * shape.head_dim
+
+
+def test_random_ragged_batches_match_the_oracle():
+    """Twenty seeded random hybrid batches on a small two-layer shape -- decode rows, chunks of every length up to a
+    few pages at arbitrary cached lengths, in arbitrary order -- against the oracle: output within the tolerance,
+    exactly the new tokens' slots written."""
+    shape = synth.StageShape("ragged", 2, 256, 8, 2, 64, 384)
+    w = layer_weights_np(shape, 33)
+    rng = np.random.default_rng(33)
+    sizing = synth.build_batch([(70, 130)] * 10, 1)
+    stage = GpuStage(shape, w, [sizing])
+    for case in range(20):
+        n_seq = int(rng.integers(1, 11))
+        seqs = []
+        for _ in range(n_seq):
+            new = 1 if rng.random() < 0.55 else int(rng.integers(2, 71))
+            seqs.append((new, int(rng.integers(0, 131))))
+        print(f"random batch {case}: {seqs}", flush=True)
+        batch = synth.build_batch(seqs, 100 + case, spare_blocks=int(rng.integers(0, 4)), max_blocks_per_seq=sizing.block_tables.shape[1])
+        kp0, vp0 = sentinel_pool_with_prefixes(shape, batch, 100 + case)
+        r = run_both(shape, w, batch, kp0, vp0, hidden_np(shape, 100 + case, batch.num_tokens), stage)
+        assert_output(f"ragged{case}", r, literal=False)
+        mk, mv = written_mask(shape, batch)
+        check_pool("K", r["gk"], kp0, r["kp"], shape.num_layers, mask=mk)
+        check_pool("V", r["gv"], vp0, r["vp"], shape.num_layers, mask=mv)
