@@ -2,7 +2,7 @@
 """The four projections of one layer as single GEMM operations (gllm_op_gemm_bf16 / _splitk with the planner's tile
 and split), weights rotating through HBM so that they are never cache-resident, in a sustained loop.
 
-    python bench_gemm.py [--config llama3_8b_pp4] [--rows T] [--seconds S]
+    python bench_gemm.py [--config llama3_8b_pp4] [--rows T] [--seconds S] [--only gate_up_swiglu]
 
 Prints one JSON line: TFLOP/s per projection (HIP events around a run of launches of that projection alone) and the
 sustained figure of the mixed loop (wall clock over S seconds).  The sustained loop is what a power or clock reading
@@ -24,6 +24,7 @@ def main():
     ap.add_argument("--config", default="llama3_8b_pp4")
     ap.add_argument("--rows", type=int, default=2048)
     ap.add_argument("--seconds", type=float, default=5.0)
+    ap.add_argument("--only", default="", help="one of qkv, o, gate_up_swiglu, down: only this projection in the loop")
     args = ap.parse_args()
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -36,6 +37,8 @@ def main():
     # name -> (n, k, mode, max splits)
     problems = {"qkv": (n_qkv, H, B.GEMM_STORE_F32, 8), "o": (pad(H, 256), q_dim, B.GEMM_STORE_F32, 8),
                 "gate_up_swiglu": (2 * pad(I, 128), H, B.GEMM_SWIGLU_BF16, 1), "down": (pad(H, 256), pad(I, 128), B.GEMM_STORE_F32, 8)}
+    if args.only:
+        problems = {args.only: problems[args.only]}
     runs = {}
     for name, (n, k, mode, ms) in problems.items():
         tile, splits = B.gllm_op_gemm_plan(T, n, k, mode, ms)
