@@ -54,8 +54,8 @@ enum {
 typedef struct gllm_stage gllm_stage;
 
 /* Shape and limits of a stage.  Supported: page_size == 16; head_dim in {64, 128};
- * n_q_heads a multiple of n_kv_heads with at most 16 query heads per KV head; hidden and
- * n_q_heads*head_dim multiples of 64; intermediate a multiple of 8. */
+ * n_q_heads a multiple of n_kv_heads with at most 16 query heads per KV head; hidden a multiple of 128;
+ * n_q_heads*head_dim a multiple of 64; intermediate a multiple of 8.  Anything else gives GLLM_E_UNSUPPORTED. */
 typedef struct {
     int32_t num_layers;
     int32_t hidden;
@@ -154,8 +154,14 @@ gllm_status gllm_stage_set_alias_check(gllm_stage* stage, int32_t on);
  *   streams onto a few hardware queues; when the side stream happens to share the caller's queue the two kernels
  *   simply run one after the other.  Callers that run several stages on several streams of their own may do better
  *   with 0: every further stream competes for those queues.)
- *   "gemm_row_mixed" (default 1; process-wide, not per stage): the GEMM planner may cover a last band of at most
- *   128 token rows with 64- or 128-row tiles instead of a whole band of 256 (tile 8 of gllm_op_gemm_bf16).
+ *   "gemm_row_mixed" (default 1; a property of this stage only): the stage's GEMM planner may cover a last band of at
+ *   most 128 token rows with 64- or 128-row tiles instead of a whole band of 256 (tile 8 of gllm_op_gemm_bf16).
+ *   "layer_begin" (default 0), "layer_end" (default num_layers): forward() runs only layers layer_begin .. layer_end-1
+ *   of the stage, each with its own weights and its own slice of the KV pool: hidden_in is taken as the residual
+ *   stream in front of layer_begin, hidden_out is the stream behind layer_end-1.  For testing one layer at its real
+ *   shape with the activations the layers before it produce, and for timing a part of a stage.  layer_begin must lie
+ *   in [0, num_layers), layer_end in [1, num_layers] (else GLLM_E_INVALID, nothing changes); the range never becomes
+ *   empty: setting one end at or past the other moves the other so that exactly one layer is left.
  * Unknown names give GLLM_E_INVALID. */
 gllm_status gllm_stage_set_option(gllm_stage* stage, const char* name /*HOST*/, int64_t value);
 

@@ -58,6 +58,20 @@ class gllm_batch(C.Structure):
 
 
 _lib = None
+_host_lib = None
+
+
+def load_host_library():
+    """The library that holds the host-only entry points (scheduler, KV page pool).
+
+    Normally that is libgllm_stage.so itself.  GLLM_HOST_LIBRARY may name another build of the two host sources
+    (csrc/gllm_sched.cpp, csrc/gllm_kv.cpp) instead -- the sanitizer build of build.build_host_sanitized(), which
+    the CPU tests run the parity suites against; such a library is loaded without touching torch or HIP."""
+    global _host_lib
+    if _host_lib is None:
+        path = os.environ.get("GLLM_HOST_LIBRARY")
+        _host_lib = C.CDLL(path) if path else load_library()
+    return _host_lib
 
 
 def load_library():

@@ -53,5 +53,28 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+HOST_SOURCES = ["gllm_sched.cpp", "gllm_kv.cpp"]
+HOST_SAN_LIB = os.path.join(BUILD_DIR, "libgllm_host_san.so")
+
+
+def build_host_sanitized() -> str:
+    """The host-only sources (scheduler, KV page pool) as a library of their own with AddressSanitizer and
+    UndefinedBehaviorSanitizer (g++, CPU only); a process that loads it must have the ASan runtime preloaded."""
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    cxx = shutil.which("g++") or "g++"
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-fPIC", "-shared", "-Wall", "-o", HOST_SAN_LIB,
+           *[os.path.join(CSRC, f) for f in HOST_SOURCES]]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"sanitizer build failed:\n{r.stdout}\n{r.stderr}")
+    return HOST_SAN_LIB
+
+
+def sanitizer_runtime() -> str:
+    cxx = shutil.which("g++") or "g++"
+    return subprocess.run([cxx, "-print-file-name=libasan.so"], capture_output=True, text=True, check=True).stdout.strip()
+
+
 if __name__ == "__main__":
     build()

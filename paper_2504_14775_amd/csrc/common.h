@@ -44,10 +44,10 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
                             hipStream_t stream);
 int gemm_mixed_rem_cols(int m, int n);
 int gemm_rowmix_rem_rows(int m, int n);
-void gemm_plan_row_mixed(bool on);  // whether gemm_plan() may pick tile 8 (process-wide; on by default)
-// Tile id and split-K factor the cost model prefers (splits stays 1 unless mode is GEMM_STORE_F32).
+// Tile id and split-K factor the cost model prefers (splits stays 1 unless mode is GEMM_STORE_F32); row_mixed says
+// whether it may pick tile 8.
 struct GemmPlan { int tile; int splits; };
-GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits);
+GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits, bool row_mixed = true);
 
 // Residual stream entry: x = float(in_bf16), h = bf16(rmsnorm(x) * gamma).
 hipError_t launch_rmsnorm_from_bf16(const bf16_t* in, float* x, const bf16_t* gamma, bf16_t* h, int64_t ldh,

@@ -85,6 +85,8 @@ struct gllm_stage {
     hipEvent_t fork_ev[8] = {}, join_ev[8] = {};
     bool overlap_attention = true;
     bool alias_check = true;
+    bool gemm_row_mixed = true;  // the GEMM planner may cover a short last row band with 64- or 128-row tiles
+    int layer_begin = 0, layer_end = 0;  // forward() runs layers [layer_begin, layer_end) (layer_end is set at creation)
     int64_t decode_min_workgroups = 2048;  // partition the keys of decode rows until at least this many workgroups exist
     // profiling
     bool profiling = false;
@@ -257,6 +259,7 @@ gllm_status gllm_stage_create(const gllm_stage_config* cfg, gllm_stage** out) {
     s->max_pre_items = c.max_tokens / s->pre_rows + c.max_seqs + 1;
     s->max_v_tiles = c.max_tokens / kPage + 2 * c.max_seqs + 1;
     s->layers.resize(c.num_layers);
+    s->layer_end = c.num_layers;
 
     auto bail = [&](hipError_t err, const char* what) {
         gllm_status st = hip_fail(nullptr, err, what);
@@ -413,8 +416,20 @@ gllm_status gllm_stage_set_option(gllm_stage* s, const char* name, int64_t value
         s->overlap_attention = value != 0;
         return GLLM_OK;
     }
-    if (std::strcmp(name, "gemm_row_mixed") == 0) {  // process-wide: the planner is shared by all stages
-        gemm_plan_row_mixed(value != 0);
+    if (std::strcmp(name, "gemm_row_mixed") == 0) {
+        s->gemm_row_mixed = value != 0;
+        return GLLM_OK;
+    }
+    if (std::strcmp(name, "layer_begin") == 0) {
+        if (value < 0 || value >= s->cfg.num_layers) return fail(s, GLLM_E_INVALID, "layer_begin outside [0, num_layers)");
+        s->layer_begin = (int)value;
+        if (s->layer_end <= s->layer_begin) s->layer_end = s->layer_begin + 1;
+        return GLLM_OK;
+    }
+    if (std::strcmp(name, "layer_end") == 0) {
+        if (value < 1 || value > s->cfg.num_layers) return fail(s, GLLM_E_INVALID, "layer_end outside [1, num_layers]");
+        s->layer_end = (int)value;
+        if (s->layer_begin >= s->layer_end) s->layer_begin = s->layer_end - 1;
         return GLLM_OK;
     }
     if (std::strcmp(name, "decode_min_workgroups") == 0) {
@@ -458,7 +473,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     if (!b || !hidden_in || !hidden_out) return fail(s, GLLM_E_INVALID, "null argument");
     if (!s->ws) return fail(s, GLLM_E_STATE, "workspace not bound");
     if (!s->k_pool) return fail(s, GLLM_E_STATE, "KV pool not bound");
-    for (int l = 0; l < c.num_layers; ++l)
+    for (int l = s->layer_begin; l < s->layer_end; ++l)
         if (!s->layers[l].loaded) return fail(s, GLLM_E_STATE, "layer " + std::to_string(l) + " not loaded");
     const int S = b->num_seqs;
     if (S < 0 || (S > 0 && (!b->new_tokens || !b->cached_len || !b->block_tables)))
@@ -623,17 +638,19 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
     const float eps = (float)c.rms_eps;
     const int64_t y_plane = (int64_t)c.max_tokens * H;
     // tile shapes and split-K factors for this batch size (the consumers sum the partial planes in order)
-    const GemmPlan plan_qkv = gemm_plan(Ti, s->n_qkv_pad, H, GEMM_STORE_F32, kMaxSplits);
-    const GemmPlan plan_o = gemm_plan(Ti, H, s->q_dim, GEMM_STORE_F32, kMaxSplits);
-    const GemmPlan plan_d = gemm_plan(Ti, H, s->inter_pad, GEMM_STORE_F32, kMaxSplits);
+    const bool rm = s->gemm_row_mixed;
+    const GemmPlan plan_qkv = gemm_plan(Ti, s->n_qkv_pad, H, GEMM_STORE_F32, kMaxSplits, rm);
+    const GemmPlan plan_o = gemm_plan(Ti, H, s->q_dim, GEMM_STORE_F32, kMaxSplits, rm);
+    const GemmPlan plan_gu = gemm_plan(Ti, 2 * s->inter_pad, H, GEMM_SWIGLU_BF16, 1, rm);
+    const GemmPlan plan_d = gemm_plan(Ti, H, s->inter_pad, GEMM_STORE_F32, kMaxSplits, rm);
     const int split_o = plan_o.splits, split_d = plan_d.splits;
     const int64_t qkv_plane = (int64_t)c.max_tokens * s->n_qkv_pad;
     int pending = 0;  // planes of y still to be added to the residual stream
-    for (int l = 0; l < c.num_layers; ++l) {
+    for (int l = s->layer_begin; l < s->layer_end; ++l) {
         const LayerBuffers& L = s->layers[l];
         {
             ProfScope ps(s, st, PC_RMSNORM);
-            if (l == 0) HIP_TRY(s, launch_rmsnorm_from_bf16((const bf16_t*)hidden_in, s->x, L.norm1, s->h, H, Ti, H, eps, st));
+            if (l == s->layer_begin) HIP_TRY(s, launch_rmsnorm_from_bf16((const bf16_t*)hidden_in, s->x, L.norm1, s->h, H, Ti, H, eps, st));
             else HIP_TRY(s, launch_add_rmsnorm(s->x, s->y, pending, y_plane, L.norm1, s->h, H, Ti, H, eps, st));
         }
         {
@@ -692,7 +709,7 @@ gllm_status gllm_stage_forward(gllm_stage* s, const gllm_batch* b, const void* h
         }
         {
             ProfScope ps(s, st, PC_GEMM_GATEUP);
-            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wgu, H, s->act, s->inter_pad, Ti, 2 * s->inter_pad, H, GEMM_SWIGLU_BF16, -1, 1, 0, st));
+            HIP_TRY(s, launch_gemm_bf16(s->h, H, L.wgu, H, s->act, s->inter_pad, Ti, 2 * s->inter_pad, H, GEMM_SWIGLU_BF16, plan_gu.tile, 1, 0, st));
         }
         {
             ProfScope ps(s, st, PC_GEMM_DOWN);

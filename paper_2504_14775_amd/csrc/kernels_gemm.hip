@@ -397,9 +397,6 @@ hipError_t launch_rowmix(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t 
 
 // Height of the last row band for a row-mixed launch (64 or 128), or 0 when the shape does not call for one: at
 // least one whole band of 256 rows and at most 128 rows left over.
-static bool g_rowmix_planned = true;
-void gemm_plan_row_mixed(bool on) { g_rowmix_planned = on; }
-
 int gemm_rowmix_rem_rows(int m, int n) {
     if (n % 256 != 0 || m <= 256) return 0;
     const int r = m % 256;
@@ -429,7 +426,7 @@ int gemm_mixed_rem_cols(int m, int n) {
 // compute unit, 64 KiB of weights in flight on each, half the activation traffic of a 128-row tile) costs
 // 0.30 k_steps per tile, but not less than the weights take at 5.5 TB/s, plus 2; measured 20-35 % faster than
 // every other shape there, so it is the only candidate for such problems and the model only picks its split.
-GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
+GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits, bool row_mixed) {
     const int its = k / BK;
     GemmPlan best{0, 1};
     double best_cost = 1e30;
@@ -439,7 +436,7 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits) {
         const double steps = (double)its / s;
         const double plane_cost = (double)m * n * 4.0 * s / 8e12 / 1.65e-6;  // mostly hidden under other tiles
         const bool skinny = m <= 64 && n % 128 == 0;
-        if (g_rowmix_planned && gemm_rowmix_rem_rows(m, n) > 0) {
+        if (row_mixed && gemm_rowmix_rem_rows(m, n) > 0) {
             // (evaluated first: on equal cost it is kept -- whole rounds hide that it always does less work)
             // whole bands as 256x256 tiles; the last band's tiles go first into the compute units the last round of
             // big tiles leaves idle; those that do not fit there stream their weights from HBM once more and cost

@@ -6,7 +6,7 @@ from typing import List
 
 import numpy as np
 
-from .binding import GLLM_OK, GllmError, load_library
+from .binding import GLLM_OK, GllmError, load_host_library
 
 EXPORTS = [
     "gllm_kv_create", "gllm_kv_destroy", "gllm_kv_available", "gllm_kv_alloc", "gllm_kv_match", "gllm_kv_register",
@@ -25,7 +25,7 @@ _ready = False
 
 def _lib():
     global _ready
-    lib = load_library()
+    lib = load_host_library()
     if not _ready:
         i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
         P = C.POINTER

@@ -7,7 +7,7 @@ from typing import List, Optional, Tuple
 
 import numpy as np
 
-from .binding import GLLM_OK, GllmError, load_library
+from .binding import GLLM_OK, GllmError, load_host_library
 
 EXPORTS = [
     "gllm_sched_prefill_budget", "gllm_sched_decode_budget", "gllm_sched_create", "gllm_sched_destroy",
@@ -66,7 +66,7 @@ _ready = False
 
 def _lib():
     global _ready
-    lib = load_library()
+    lib = load_host_library()
     if not _ready:
         i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
         P = C.POINTER

@@ -47,6 +47,7 @@ def test_create_rejects_bad_configs_before_touching_a_device():
         (dict(head_dim=96), -7),
         (dict(n_q_heads=5), -7),
         (dict(hidden=200), -7),
+        (dict(hidden=192), -7),          # a multiple of 64 but not of 128: the header states 128
         (dict(num_layers=0), -1),
     ]:
         cfg = B.make_config(dataclasses.replace(shape, **bad), 64, 8, 8, 128)

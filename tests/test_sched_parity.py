@@ -25,7 +25,7 @@ def both(**kw):
 def test_library_exports_every_function_the_header_declares():
     text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
     declared = sorted(set(re.findall(r"\b(gllm_sched_[a-z0-9_]+)\s*\(", text)))
-    lib = B.load_library()
+    lib = B.load_host_library()
     for n in declared:
         assert hasattr(lib, n), n
     assert set(declared) == set(S.EXPORTS)
