@@ -61,6 +61,7 @@ def lib():
             f.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int]
         _lib.oracle_token_map.restype = C.c_int64
         _lib.oracle_stage_forward.restype = C.c_int
+        _lib.oracle_layer_rows.restype = C.c_int
     return _lib
 
 
@@ -226,3 +227,33 @@ def stage_forward(shape, layers: Sequence[Dict[str, np.ndarray]], new_tokens, ca
     if rc != 0:
         raise ValueError(f"oracle_stage_forward rejected the batch (rc={rc})")
     return out, outb
+
+
+def layer_rows(shape, layer: int, weights: Dict[str, np.ndarray], new_tokens, cached_len, block_tables,
+               num_pages: int, k_pool: np.ndarray, v_pool: np.ndarray, hidden_bits: np.ndarray,
+               need: Optional[np.ndarray] = None, round_operands: bool = False) -> np.ndarray:
+    """Layer `layer` of the stage alone (its weights, its slice of the pools, which hold all layers of `shape`).
+
+    hidden_bits [T,H] is the residual stream in front of the layer (bf16 bits); need [T] (bool, None = all) selects
+    the rows that are carried through the layer; every row writes its K and V into the pools (updated in place).
+    Returns out_f64 [T,H]: the stream behind the layer on the needed rows, the widened input elsewhere.
+    """
+    cfg = make_config(shape, round_operands)
+    lay = make_layer(weights)
+    nt, cl, bt = _i32(new_tokens), _i32(cached_len), _i32(block_tables)
+    T = int(nt.sum())
+    hid = _u16(hidden_bits)
+    assert hid.shape == (T, shape.hidden)
+    assert k_pool.dtype == np.uint16 and v_pool.dtype == np.uint16
+    assert k_pool.flags.c_contiguous and v_pool.flags.c_contiguous
+    nd = None
+    if need is not None:
+        nd = np.ascontiguousarray(need, dtype=np.uint8)
+        assert nd.shape == (T,)
+    out = np.empty((T, shape.hidden), dtype=np.float64)
+    rc = lib().oracle_layer_rows(C.byref(cfg), C.c_int(layer), C.byref(lay), C.c_int(len(nt)), _p(nt), _p(cl), _p(bt),
+                                 C.c_int(bt.shape[1]), C.c_int64(num_pages), _p(k_pool), _p(v_pool), _p(hid),
+                                 _p(nd), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_layer_rows rejected the batch (rc={rc})")
+    return out

@@ -315,52 +315,93 @@ void oracle_swiglu(int64_t count, const double *gate, const double *up, double *
 
 /* ---------------------------------------------------------------- one decoder layer
  * x [T][H] is the residual stream (in place).  tap, if not NULL, receives the residual
- * stream after the attention half ([T][H]).                                               */
+ * stream after the attention half ([T][H]).
+ *
+ * need (may be NULL = every row): only the rows t with need[t] != 0 are carried through the
+ * layer; the others only contribute what later rows of their sequence can see of them -- their K
+ * and V in the pool -- and their x (and tap) rows are left as they were.  A row's result depends
+ * on its own x and on the pool alone, and every step function forms each output element by the
+ * same sequence of operations whatever other rows are present, so a needed row comes out bit for
+ * bit as it does with need = NULL.  This is how a few rows deep inside a long prefill chunk are
+ * checked at real shapes without paying for the projections of the whole chunk.            */
+static void gather_rows(int64_t n, const int64_t *idx, int64_t width, const double *src, double *dst)
+{
+    for (int64_t i = 0; i < n; ++i) memcpy(dst + i * width, src + idx[i] * width, (size_t)width * sizeof(double));
+}
+
+static void layer_forward_rows(const oracle_config *c, int layer, const oracle_layer *w, int64_t T,
+                               const int32_t *seq_of, const int32_t *pos_of, const int32_t *block_tables,
+                               int max_blocks_per_seq, int64_t num_pages, uint16_t *k_pool,
+                               uint16_t *v_pool, double *x, double *tap, const uint8_t *need)
+{
+    int H = c->hidden, d = c->head_dim, I = c->intermediate;
+    int QD = c->n_q_heads * d, KD = c->n_kv_heads * d;
+    int64_t *idx = (int64_t *)malloc((size_t)(T + 1) * sizeof(int64_t));
+    int64_t Tn = 0;
+    for (int64_t t = 0; t < T; ++t)
+        if (!need || need[t]) idx[Tn++] = t;
+    int32_t *seq_n = (int32_t *)malloc((size_t)(Tn + 1) * sizeof(int32_t));
+    int32_t *pos_n = (int32_t *)malloc((size_t)(Tn + 1) * sizeof(int32_t));
+    for (int64_t i = 0; i < Tn; ++i) {
+        seq_n[i] = seq_of[idx[i]];
+        pos_n[i] = pos_of[idx[i]];
+    }
+    double *h = (double *)malloc((size_t)(T * H + 1) * sizeof(double));
+    double *k = (double *)malloc((size_t)(T * KD + 1) * sizeof(double));
+    double *v = (double *)malloc((size_t)(T * KD + 1) * sizeof(double));
+    double *xs = (double *)malloc((size_t)(Tn * H + 1) * sizeof(double));
+    double *hs = (double *)malloc((size_t)(Tn * H + 1) * sizeof(double));
+    double *q = (double *)malloc((size_t)(Tn * QD + 1) * sizeof(double));
+    double *o = (double *)malloc((size_t)(Tn * QD + 1) * sizeof(double));
+    double *y = (double *)malloc((size_t)(Tn * H + 1) * sizeof(double));
+    double *gt = (double *)malloc((size_t)(Tn * I + 1) * sizeof(double));
+    double *up = (double *)malloc((size_t)(Tn * I + 1) * sizeof(double));
+
+    /* every row: h = rmsnorm(x), K and V of its position into the pool */
+    oracle_rmsnorm(T, H, x, w->norm1, c->rms_eps, h);
+    if (c->round_operands) round_through_bf16(T * (int64_t)H, h);
+    oracle_linear(T, H, KD, h, w->wk, c->has_qkv_bias ? w->bk : NULL, k);
+    oracle_linear(T, H, KD, h, w->wv, c->has_qkv_bias ? w->bv : NULL, v);
+    oracle_rope(T, c->n_kv_heads, d, pos_of, c->rope_theta, k);
+    oracle_kv_write(c, layer, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages, k, v,
+                    k_pool, v_pool);
+
+    /* needed rows, attention half: x += Wo . attention(rope(Wq h), pool) */
+    gather_rows(Tn, idx, H, x, xs);
+    gather_rows(Tn, idx, H, h, hs);
+    oracle_linear(Tn, H, QD, hs, w->wq, c->has_qkv_bias ? w->bq : NULL, q);
+    oracle_rope(Tn, c->n_q_heads, d, pos_n, c->rope_theta, q);
+    if (c->round_operands) round_through_bf16(Tn * (int64_t)QD, q);
+    oracle_attention(c, layer, Tn, seq_n, pos_n, block_tables, max_blocks_per_seq, num_pages, q,
+                     k_pool, v_pool, o);
+    if (c->round_operands) round_through_bf16(Tn * (int64_t)QD, o);
+    oracle_linear(Tn, QD, H, o, w->wo, NULL, y);
+    for (int64_t i = 0; i < Tn * H; ++i) xs[i] += y[i];
+    if (tap)
+        for (int64_t i = 0; i < Tn; ++i) memcpy(tap + idx[i] * H, xs + i * H, (size_t)H * sizeof(double));
+
+    /* needed rows, MLP half: x += Wd . (silu(Wg h2) * (Wu h2)) with h2 = rmsnorm(x) */
+    oracle_rmsnorm(Tn, H, xs, w->norm2, c->rms_eps, hs);
+    if (c->round_operands) round_through_bf16(Tn * (int64_t)H, hs);
+    oracle_linear(Tn, H, I, hs, w->wgate, NULL, gt);
+    oracle_linear(Tn, H, I, hs, w->wup, NULL, up);
+    oracle_swiglu(Tn * (int64_t)I, gt, up, gt);
+    if (c->round_operands) round_through_bf16(Tn * (int64_t)I, gt);
+    oracle_linear(Tn, I, H, gt, w->wdown, NULL, y);
+    for (int64_t i = 0; i < Tn * H; ++i) xs[i] += y[i];
+    for (int64_t i = 0; i < Tn; ++i) memcpy(x + idx[i] * H, xs + i * H, (size_t)H * sizeof(double));
+
+    free(idx); free(seq_n); free(pos_n);
+    free(h); free(k); free(v); free(xs); free(hs); free(q); free(o); free(y); free(gt); free(up);
+}
+
 void oracle_layer_forward(const oracle_config *c, int layer, const oracle_layer *w, int64_t T,
                           const int32_t *seq_of, const int32_t *pos_of, const int32_t *block_tables,
                           int max_blocks_per_seq, int64_t num_pages, uint16_t *k_pool,
                           uint16_t *v_pool, double *x, double *tap)
 {
-    int H = c->hidden, d = c->head_dim, I = c->intermediate;
-    int QD = c->n_q_heads * d, KD = c->n_kv_heads * d;
-    double *h = (double *)malloc((size_t)T * H * sizeof(double));
-    double *q = (double *)malloc((size_t)T * QD * sizeof(double));
-    double *k = (double *)malloc((size_t)T * KD * sizeof(double));
-    double *v = (double *)malloc((size_t)T * KD * sizeof(double));
-    double *o = (double *)malloc((size_t)T * QD * sizeof(double));
-    double *y = (double *)malloc((size_t)T * H * sizeof(double));
-    double *gt = (double *)malloc((size_t)T * I * sizeof(double));
-    double *up = (double *)malloc((size_t)T * I * sizeof(double));
-
-    /* attention half: x += Wo . attention(rope(Wq h), pool) with h = rmsnorm(x) */
-    oracle_rmsnorm(T, H, x, w->norm1, c->rms_eps, h);
-    if (c->round_operands) round_through_bf16(T * (int64_t)H, h);
-    oracle_linear(T, H, QD, h, w->wq, c->has_qkv_bias ? w->bq : NULL, q);
-    oracle_linear(T, H, KD, h, w->wk, c->has_qkv_bias ? w->bk : NULL, k);
-    oracle_linear(T, H, KD, h, w->wv, c->has_qkv_bias ? w->bv : NULL, v);
-    oracle_rope(T, c->n_q_heads, d, pos_of, c->rope_theta, q);
-    oracle_rope(T, c->n_kv_heads, d, pos_of, c->rope_theta, k);
-    if (c->round_operands) round_through_bf16(T * (int64_t)QD, q);
-    oracle_kv_write(c, layer, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages, k, v,
-                    k_pool, v_pool);
-    oracle_attention(c, layer, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages, q,
-                     k_pool, v_pool, o);
-    if (c->round_operands) round_through_bf16(T * (int64_t)QD, o);
-    oracle_linear(T, QD, H, o, w->wo, NULL, y);
-    for (int64_t i = 0; i < T * H; ++i) x[i] += y[i];
-    if (tap) memcpy(tap, x, (size_t)T * H * sizeof(double));
-
-    /* MLP half: x += Wd . (silu(Wg h2) * (Wu h2)) with h2 = rmsnorm(x) */
-    oracle_rmsnorm(T, H, x, w->norm2, c->rms_eps, h);
-    if (c->round_operands) round_through_bf16(T * (int64_t)H, h);
-    oracle_linear(T, H, I, h, w->wgate, NULL, gt);
-    oracle_linear(T, H, I, h, w->wup, NULL, up);
-    oracle_swiglu(T * (int64_t)I, gt, up, gt);
-    if (c->round_operands) round_through_bf16(T * (int64_t)I, gt);
-    oracle_linear(T, I, H, gt, w->wdown, NULL, y);
-    for (int64_t i = 0; i < T * H; ++i) x[i] += y[i];
-
-    free(h); free(q); free(k); free(v); free(o); free(y); free(gt); free(up);
+    layer_forward_rows(c, layer, w, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages,
+                       k_pool, v_pool, x, tap, NULL);
 }
 
 /* ---------------------------------------------------------------- the stage
@@ -368,22 +409,30 @@ void oracle_layer_forward(const oracle_config *c, int layer, const oracle_layer 
  * out_bf16 (may be NULL): the same rounded to bf16.  The pools are updated in place.
  * Returns 0, or -1 on a malformed batch (a page id outside the pool, a non-positive
  * new-token count, a negative cached length).                                             */
+static int batch_is_valid(const oracle_config *c, int S, const int32_t *new_tokens, const int32_t *cached_len,
+                          const int32_t *block_tables, int max_blocks_per_seq, int64_t num_pages)
+{
+    int ps = c->page_size;
+    for (int s = 0; s < S; ++s) {
+        if (new_tokens[s] < 1 || cached_len[s] < 0) return 0;
+        int nb = (new_tokens[s] + cached_len[s] + ps - 1) / ps;
+        if (nb > max_blocks_per_seq) return 0;
+        for (int b = 0; b < nb; ++b) {
+            int64_t pg = block_tables[(int64_t)s * max_blocks_per_seq + b];
+            if (pg < 0 || pg >= num_pages) return 0;
+        }
+    }
+    return 1;
+}
+
 int oracle_stage_forward(const oracle_config *c, const oracle_layer *layers, int S,
                          const int32_t *new_tokens, const int32_t *cached_len,
                          const int32_t *block_tables, int max_blocks_per_seq, int64_t num_pages,
                          uint16_t *k_pool, uint16_t *v_pool, const uint16_t *hidden_in,
                          double *out_f64, uint16_t *out_bf16)
 {
-    int H = c->hidden, ps = c->page_size;
-    for (int s = 0; s < S; ++s) {
-        if (new_tokens[s] < 1 || cached_len[s] < 0) return -1;
-        int nb = (new_tokens[s] + cached_len[s] + ps - 1) / ps;
-        if (nb > max_blocks_per_seq) return -1;
-        for (int b = 0; b < nb; ++b) {
-            int64_t pg = block_tables[(int64_t)s * max_blocks_per_seq + b];
-            if (pg < 0 || pg >= num_pages) return -1;
-        }
-    }
+    int H = c->hidden;
+    if (!batch_is_valid(c, S, new_tokens, cached_len, block_tables, max_blocks_per_seq, num_pages)) return -1;
     int64_t T = oracle_token_map(S, new_tokens, cached_len, NULL, NULL);
     int32_t *seq_of = (int32_t *)malloc((size_t)(T + 1) * sizeof(int32_t));
     int32_t *pos_of = (int32_t *)malloc((size_t)(T + 1) * sizeof(int32_t));
@@ -397,5 +446,30 @@ int oracle_stage_forward(const oracle_config *c, const oracle_layer *layers, int
     if (out_bf16)
         for (int64_t i = 0; i < T * H; ++i) out_bf16[i] = oracle_f64_to_bf16(x[i]);
     free(x); free(seq_of); free(pos_of);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- one layer of a stage, some rows
+ * The stage reduced to its layer `layer` (weights w, that layer's slice of the pools): hidden_in
+ * bf16 [T][H] is the residual stream in front of the layer; out_f64 [T][H] receives the stream
+ * behind it for the rows with need[t] != 0 (all rows if need is NULL) and the widened input for
+ * the others; every row writes its K and V.  Returns 0, or -1 on a malformed batch.          */
+int oracle_layer_rows(const oracle_config *c, int layer, const oracle_layer *w, int S,
+                      const int32_t *new_tokens, const int32_t *cached_len,
+                      const int32_t *block_tables, int max_blocks_per_seq, int64_t num_pages,
+                      uint16_t *k_pool, uint16_t *v_pool, const uint16_t *hidden_in,
+                      const uint8_t *need, double *out_f64)
+{
+    int H = c->hidden;
+    if (layer < 0 || layer >= c->num_layers) return -1;
+    if (!batch_is_valid(c, S, new_tokens, cached_len, block_tables, max_blocks_per_seq, num_pages)) return -1;
+    int64_t T = oracle_token_map(S, new_tokens, cached_len, NULL, NULL);
+    int32_t *seq_of = (int32_t *)malloc((size_t)(T + 1) * sizeof(int32_t));
+    int32_t *pos_of = (int32_t *)malloc((size_t)(T + 1) * sizeof(int32_t));
+    oracle_token_map(S, new_tokens, cached_len, seq_of, pos_of);
+    for (int64_t i = 0; i < T * H; ++i) out_f64[i] = oracle_bf16_to_f64(hidden_in[i]);
+    layer_forward_rows(c, layer, w, T, seq_of, pos_of, block_tables, max_blocks_per_seq, num_pages,
+                       k_pool, v_pool, out_f64, NULL, need);
+    free(seq_of); free(pos_of);
     return 0;
 }

@@ -158,8 +158,17 @@ def _bf16_round(a):
     return oracle.bf16_to_f64(oracle.f64_to_bf16(a))
 
 
-def _dense_layer(shape, w, x):
-    """One decoder layer on a single full sequence, unpaged, from dense library matmuls."""
+ROUNDING_POINTS = ("h", "q", "o", "h2", "act")
+
+
+def _dense_layer(shape, w, x, round_at=()):
+    """One decoder layer on a single full sequence, unpaged, from dense library matmuls.
+
+    round_at names the tensors that are rounded to bf16 on the way: "h" / "h2" the normalised activations in front
+    of the QKV / gate-up projections, "q" the rotated queries, "o" the attention output, "act" the SwiGLU output
+    (ROUNDING_POINTS: what the oracle's diagnostic reading rounds), and for the negative checks "x_mid" the residual
+    stream after attention, "gate_up" the two MLP projections, "k_pre" the keys before their rotation."""
+    r = lambda name, a: _bf16_round(a) if name in round_at else a
     f = {k: oracle.bf16_to_f64(v) for k, v in w.items()}
     n, H = x.shape
     d, nq, nkv = shape.head_dim, shape.n_q_heads, shape.n_kv_heads
@@ -172,9 +181,9 @@ def _dense_layer(shape, w, x):
         c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
         lo, hi = a[..., : d // 2], a[..., d // 2:]
         return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
-    h = norm(x, f["norm1"])
-    q = rot(h @ f["wq"].T, nq)
-    k = _bf16_round(rot(h @ f["wk"].T, nkv))
+    h = r("h", norm(x, f["norm1"]))
+    q = r("q", rot(h @ f["wq"].T, nq))
+    k = _bf16_round(rot(r("k_pre", h @ f["wk"].T), nkv))
     v = _bf16_round((h @ f["wv"].T).reshape(n, nkv, d))
     o = np.zeros((n, nq, d))
     mask = np.tril(np.ones((n, n), dtype=bool))
@@ -183,10 +192,10 @@ def _dense_layer(shape, w, x):
         S = np.where(mask, S, -np.inf)
         P = np.exp(S - S.max(axis=1, keepdims=True)); P /= P.sum(axis=1, keepdims=True)
         o[:, hq] = P @ v[:, hq // (nq // nkv)]
-    x = x + o.reshape(n, nq * d) @ f["wo"].T
-    h2 = norm(x, f["norm2"])
-    gate, up = h2 @ f["wgate"].T, h2 @ f["wup"].T
-    return x + (gate / (1 + np.exp(-gate)) * up) @ f["wdown"].T
+    x = r("x_mid", x + r("o", o.reshape(n, nq * d)) @ f["wo"].T)
+    h2 = r("h2", norm(x, f["norm2"]))
+    gate, up = r("gate_up", h2 @ f["wgate"].T), r("gate_up", h2 @ f["wup"].T)
+    return x + r("act", gate / (1 + np.exp(-gate)) * up) @ f["wdown"].T
 
 
 def test_stage_matches_dense_unpaged_layers():
@@ -201,6 +210,70 @@ def test_stage_matches_dense_unpaged_layers():
     # bf16 rounding of K/V may flip on ~1e-16 differences, hence not exact; far below any real slip
     np.testing.assert_allclose(got, ref, rtol=0, atol=2e-3 * np.abs(ref).max())
     assert np.abs(got - ref).mean() < 1e-5
+
+
+def test_diagnostic_reading_rounds_exactly_the_five_operand_tensors():
+    """Pins WHICH tensors the oracle's round_operands reading rounds to bf16: a dense restatement that rounds
+    exactly {h, q, o, h2, act} reproduces it (to the accuracy the plain reading is reproduced with); a restatement
+    that leaves any one of the five unrounded, or rounds one tensor more, is farther away by orders of magnitude."""
+    shape = small_shape(num_layers=2, hidden=48, n_q_heads=6, n_kv_heads=3, head_dim=8, intermediate=80)
+    w = layer_weights_np(shape, seed=21)
+    n = 45
+    x = hidden_np(shape, 21, n)
+    bt = np.array([[2, 0, 1]], dtype=np.int32)
+    got = oracle.stage_forward(shape, w, [n], [0], bt, 3, *fresh_pools(shape, 3), x, round_operands=True)[0]
+
+    def dense(points):
+        ref = oracle.bf16_to_f64(x)
+        for l in range(2):
+            ref = _dense_layer(shape, w[l], ref, round_at=points)
+        return ref
+
+    dist = lambda ref: float(np.abs(got - ref).mean())
+    # with bf16 operands every product is exact in double and the short sums nearly so: the restatement agrees to
+    # rounding of the last few bits, whatever the order of its sums
+    assert np.abs(got - dense(ROUNDING_POINTS)).max() < 1e-9
+    for drop in ROUNDING_POINTS:
+        d = dist(dense(tuple(p for p in ROUNDING_POINTS if p != drop)))
+        assert d > 1e-6, (drop, d)
+    for extra in ("x_mid", "gate_up", "k_pre"):
+        d = dist(dense(ROUNDING_POINTS + (extra,)))
+        assert d > 1e-6, (extra, d)
+    assert dist(dense(())) > 1e-6          # and it is not the plain reading
+
+
+def test_layer_rows_equals_the_stage_on_the_needed_rows_bitwise(weights):
+    """oracle.layer_rows (one layer of the stage, only some rows carried through) against stage_forward: needed rows
+    and the pools bit for bit, the other rows untouched, for the first and for a later layer of the stage."""
+    num_pages = 12
+    seqs = [(37, 11), (1, 30), (9, 0), (1, 15)]
+    nt, cl = [n for n, _ in seqs], [c for _, c in seqs]
+    bt = np.array([[0, 1, 6], [2, 3, -1], [4, -1, -1], [5, -1, -1]], dtype=np.int32)
+    T = sum(nt)
+    x = hidden_np(SHAPE, 31, T)
+    kp0, vp0 = pool_np(SHAPE, 31, num_pages)
+    per_layer = synth.pool_elems_per_layer(SHAPE, num_pages)
+    import dataclasses
+    one = dataclasses.replace(SHAPE, num_layers=1)
+    need = np.zeros(T, dtype=bool)
+    need[[0, 5, 20, 36, 37, 40, 46, 47]] = True            # chunk start / interior / last row, a decode row, second chunk
+    for layer in (0, 1):
+        for ro in (False, True):
+            # the stage reduced to this layer: its weights, its slice of the pools
+            k1, v1 = kp0[layer * per_layer:(layer + 1) * per_layer].copy(), vp0[layer * per_layer:(layer + 1) * per_layer].copy()
+            full = oracle.stage_forward(one, [weights[layer]], nt, cl, bt, num_pages, k1, v1, x, round_operands=ro)[0]
+            kp, vp = kp0.copy(), vp0.copy()
+            got = oracle.layer_rows(SHAPE, layer, weights[layer], nt, cl, bt, num_pages, kp, vp, x, need, round_operands=ro)
+            assert np.array_equal(got[need], full[need])
+            assert np.array_equal(got[~need], oracle.bf16_to_f64(x)[~need])
+            assert np.array_equal(kp[layer * per_layer:(layer + 1) * per_layer], k1)
+            assert np.array_equal(vp[layer * per_layer:(layer + 1) * per_layer], v1)
+            other = 1 - layer
+            assert np.array_equal(kp[other * per_layer:(other + 1) * per_layer], kp0[other * per_layer:(other + 1) * per_layer])
+            every = oracle.layer_rows(SHAPE, layer, weights[layer], nt, cl, bt, num_pages, kp0.copy(), vp0.copy(), x, None, round_operands=ro)
+            assert np.array_equal(every, full)
+    with pytest.raises(ValueError):
+        oracle.layer_rows(SHAPE, 2, weights[0], nt, cl, bt, num_pages, kp0.copy(), vp0.copy(), x, need)
 
 
 def test_malformed_batches_are_rejected(weights):
