@@ -396,3 +396,62 @@ def test_random_ragged_batches_match_the_oracle():
         mk, mv = written_mask(shape, batch)
         check_pool("K", r["gk"], kp0, r["kp"], shape.num_layers, mask=mk)
         check_pool("V", r["gv"], vp0, r["vp"], shape.num_layers, mask=mv)
+
+
+def test_layer_range_option_runs_a_part_of_the_stage():
+    """layer_begin / layer_end: layers [0, l) equal an l-layer stage of the same weights bit for bit; layer l alone
+    equals a one-layer stage holding layer l's weights over layer l's slice of the pool, bit for bit, pool included;
+    layers outside the range leave their pool slices alone."""
+    print("layer range option, 3-layer stage", flush=True)
+    shape = dataclasses.replace(synth.SHAPES["tiny"], num_layers=3)
+    batch = synth.make_batch("tiny", 0)
+    w = layer_weights_np(shape, 4)
+    kp0, vp0 = pool_np(shape, 4, batch.num_blocks)
+    x = to_dev_bits(hidden_np(shape, 4, batch.num_tokens))
+    per_layer = synth.pool_elems_per_layer(shape, batch.num_blocks)
+    whole = GpuStage(shape, w, [batch])
+    for l in (1, 2):
+        dk, dv = to_dev_bits(kp0), to_dev_bits(vp0)
+        whole.stage.set_option("layer_begin", 0)
+        whole.stage.set_option("layer_end", l)
+        head, head32 = whole.run(batch, dk, dv, x)
+        short = GpuStage(dataclasses.replace(shape, num_layers=l), w[:l], [batch])
+        sk, sv = to_dev_bits(kp0[:l * per_layer]), to_dev_bits(vp0[:l * per_layer])
+        want, want32 = short.run(batch, sk, sv, x)
+        assert torch.equal(head.view(torch.int16), want.view(torch.int16)) and torch.equal(head32, want32)
+        assert np.array_equal(bits_of(dk)[:l * per_layer], bits_of(sk)) and np.array_equal(bits_of(dv)[:l * per_layer], bits_of(sv))
+        assert np.array_equal(bits_of(dk)[l * per_layer:], kp0[l * per_layer:])        # later layers untouched
+        short.stage.destroy()
+        # layer l alone, fed the bf16 output of the layers before it
+        whole.stage.set_option("layer_begin", l)          # moves layer_end to l + 1
+        whole.stage.set_option("layer_end", l + 1)
+        dk2, dv2 = to_dev_bits(kp0), to_dev_bits(vp0)
+        tail, tail32 = whole.run(batch, dk2, dv2, head)
+        one = GpuStage(dataclasses.replace(shape, num_layers=1), [w[l]], [batch])
+        ok, ov = to_dev_bits(kp0[l * per_layer:(l + 1) * per_layer]), to_dev_bits(vp0[l * per_layer:(l + 1) * per_layer])
+        want, want32 = one.run(batch, ok, ov, head)
+        assert torch.equal(tail.view(torch.int16), want.view(torch.int16)) and torch.equal(tail32, want32)
+        assert np.array_equal(bits_of(dk2)[l * per_layer:(l + 1) * per_layer], bits_of(ok))
+        assert np.array_equal(bits_of(dk2)[:l * per_layer], kp0[:l * per_layer])
+        one.stage.destroy()
+    for name, v in (("layer_begin", -1), ("layer_begin", 3), ("layer_end", 0), ("layer_end", 4)):
+        with pytest.raises(B.GllmError):
+            whole.stage.set_option(name, v)
+    whole.stage.destroy()
+
+
+def test_row_mixed_option_belongs_to_one_stage():
+    """Two stage objects: switching gemm_row_mixed off on one must not change what the other computes or how."""
+    shape = synth.SHAPES["tiny"]
+    batch = synth.build_batch([(300, 0)], 0, label="300 rows")      # 300 rows: a band of 256 plus a short one
+    w = layer_weights_np(shape, 5)
+    kp0, vp0 = pool_np(shape, 5, batch.num_blocks)
+    x = to_dev_bits(hidden_np(shape, 5, batch.num_tokens))
+    a, b = GpuStage(shape, w, [batch]), GpuStage(shape, w, [batch])
+    ref_a = a.run(batch, to_dev_bits(kp0), to_dev_bits(vp0), x)[1]
+    b.stage.set_option("gemm_row_mixed", 0)
+    out_b = b.run(batch, to_dev_bits(kp0), to_dev_bits(vp0), x)[1]
+    out_a = a.run(batch, to_dev_bits(kp0), to_dev_bits(vp0), x)[1]
+    assert torch.equal(out_a, ref_a)                                    # a's plan is unchanged
+    assert torch.allclose(out_a, out_b, rtol=0, atol=1e-4)              # same result either way (tile shapes differ)
+    a.stage.destroy(); b.stage.destroy()
