@@ -64,6 +64,19 @@ gllm_status gllm_head_logits(gllm_head* head, const float* x, int32_t num_x_rows
                              float* logits, int64_t ld_logits, void* stream);
 int32_t gllm_head_padded_vocab(const gllm_head* head);
 
+/* gllm_head_logits for callers that cannot allocate device memory and have no workspace to bind (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results bit for
+ * bit, but the normalised bf16 rows between the two kernels live in a fixed array inside the library
+ * (gllm_head_static_scratch_bytes() = 8 MiB per GPU, held until the process ends) instead of a bound workspace.  The
+ * call allocates and frees nothing.  Limit: round_up(num_rows, 256) * hidden * 2 bytes must fit the array (512 rows
+ * at hidden 8192, 1024 at 4096), else GLLM_E_CAPACITY and nothing is enqueued; max_rows and the bound workspace of
+ * the head are not consulted.  GLLM_E_STATE before gllm_head_load.  All calls on one GPU share the one array, also
+ * across head objects and streams: calls that may overlap in time on one GPU race on it (order them on one stream
+ * or with events); nothing in it needs clearing between calls. */
+gllm_status gllm_head_logits_static(gllm_head* head, const float* x, int32_t num_x_rows, const int32_t* rows,
+                                    int32_t num_rows, float* logits, int64_t ld_logits, void* stream);
+size_t gllm_head_static_scratch_bytes(void);
+
 /* Sampling strategy (section 2.1: greedy, top-k, nucleus), one token per row of logits:
  *   temperature[i] <= 0: greedy, the lowest index among the largest logits.
  *   otherwise: z = logits / temperature; keep the top_k[i] largest z (top_k <= 0 or >= vocab keeps all; every z

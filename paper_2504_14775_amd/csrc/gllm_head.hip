@@ -4,6 +4,7 @@
 #include "common.h"
 
 #include <climits>
+#include <mutex>
 #include <string>
 
 namespace {
@@ -541,7 +542,35 @@ struct gllm_head {
     std::string err;
 };
 
+// Scratch of gllm_head_logits_static: the normalised bf16 rows between the two kernels of the projection, for callers
+// that can neither allocate nor bind a workspace.  One array per GPU, held until the process ends; its device address
+// is looked up once per device (host code must never use the array's name as an address).
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on first use there).
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 gllm_status fail(gllm_head* s, gllm_status st, const std::string& msg) {
     if (s) s->err = msg;
     return st;
@@ -577,6 +606,8 @@ gllm_status gllm_head_create(const gllm_head_config* cfg, gllm_head** out) {
         delete s;
         return GLLM_E_HIP;
     }
+    void* unused = nullptr;
+    (void)static_scratch(&unused);  // set-up time: gllm_head_logits_static finds the address ready (it retries if this failed)
     *out = s;
     return GLLM_OK;
 }
@@ -615,6 +646,20 @@ gllm_status gllm_head_load(gllm_head* s, const void* norm_gain, const void* w_vo
 
 int32_t gllm_head_padded_vocab(const gllm_head* s) { return s ? s->vocab_pad : 0; }
 
+// Both projection entry points: rows of x -> normalised bf16 rows in h_buf -> logits (h_buf must hold round_up(num_rows, 256)
+// rows, 288 for 257..288 rows; rows past num_rows are read by the GEMM's tiles and their products discarded).
+static gllm_status head_logits_into(gllm_head* s, bf16_t* h_buf, const float* x, int32_t num_x_rows, const int32_t* rows,
+                                    int32_t num_rows, float* logits, int64_t ld_logits, hipStream_t st) {
+    const int H = s->cfg.hidden;
+    gather_rmsnorm_kernel<<<num_rows, 256, 0, st>>>(x, num_x_rows, rows, s->gain, h_buf, H, (float)s->cfg.rms_eps);
+    if (hipGetLastError() != hipSuccess) return fail(s, GLLM_E_HIP, "norm launch failed");
+    const GemmPlan plan = gemm_plan(num_rows, s->vocab_pad, H, GEMM_STORE_F32, 1);
+    const hipError_t e = launch_gemm_bf16(h_buf, H, s->w, H, logits, ld_logits, num_rows, s->vocab_pad, H, GEMM_STORE_F32,
+                                          plan.tile, 1, 0, st);
+    if (e != hipSuccess) return fail(s, GLLM_E_HIP, std::string("projection launch failed: ") + hipGetErrorString(e));
+    return GLLM_OK;
+}
+
 gllm_status gllm_head_logits(gllm_head* s, const float* x, int32_t num_x_rows, const int32_t* rows, int32_t num_rows,
                              float* logits, int64_t ld_logits, void* stream) {
     if (!s || !x || !rows || !logits || num_x_rows < 1 || num_rows < 0) return GLLM_E_INVALID;
@@ -622,15 +667,26 @@ gllm_status gllm_head_logits(gllm_head* s, const float* x, int32_t num_x_rows, c
     if (num_rows > s->cfg.max_rows) return fail(s, GLLM_E_CAPACITY, "more rows than max_rows");
     if (ld_logits < s->vocab_pad || ld_logits % 4 != 0) return fail(s, GLLM_E_INVALID, "ld_logits must cover the padded vocabulary");
     if (num_rows == 0) return GLLM_OK;
-    hipStream_t st = (hipStream_t)stream;
-    const int H = s->cfg.hidden;
-    gather_rmsnorm_kernel<<<num_rows, 256, 0, st>>>(x, num_x_rows, rows, s->gain, s->h, H, (float)s->cfg.rms_eps);
-    if (hipGetLastError() != hipSuccess) return fail(s, GLLM_E_HIP, "norm launch failed");
-    const GemmPlan plan = gemm_plan(num_rows, s->vocab_pad, H, GEMM_STORE_F32, 1);
-    const hipError_t e = launch_gemm_bf16(s->h, H, s->w, H, logits, ld_logits, num_rows, s->vocab_pad, H, GEMM_STORE_F32,
-                                          plan.tile, 1, 0, st);
-    if (e != hipSuccess) return fail(s, GLLM_E_HIP, std::string("projection launch failed: ") + hipGetErrorString(e));
-    return GLLM_OK;
+    return head_logits_into(s, s->h, x, num_x_rows, rows, num_rows, logits, ld_logits, (hipStream_t)stream);
+}
+
+size_t gllm_head_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+gllm_status gllm_head_logits_static(gllm_head* s, const float* x, int32_t num_x_rows, const int32_t* rows, int32_t num_rows,
+                                    float* logits, int64_t ld_logits, void* stream) {
+    if (!s || !x || !rows || !logits || num_x_rows < 1 || num_rows < 0) return GLLM_E_INVALID;
+    if (!s->loaded) return fail(s, GLLM_E_STATE, "load the weights first");
+    if (ld_logits < s->vocab_pad || ld_logits % 4 != 0) return fail(s, GLLM_E_INVALID, "ld_logits must cover the padded vocabulary");
+    // rows the projection's tiles may read: whole bands of 256 (the one 288-row tile for 257..288 rows reads fewer)
+    const int64_t rows_read = round_up(num_rows, 256);
+    if ((size_t)rows_read * s->cfg.hidden * 2 > kStaticScratchBytes)
+        return fail(s, GLLM_E_CAPACITY, "num_rows (rounded up to the projection's row bands) x hidden x 2 bytes exceeds the " +
+                                            std::to_string(kStaticScratchBytes >> 20) + " MiB static scratch: use gllm_head_logits with a bound workspace");
+    if (num_rows == 0) return GLLM_OK;
+    void* buf = nullptr;
+    const hipError_t e = static_scratch(&buf);
+    if (e != hipSuccess) return fail(s, GLLM_E_HIP, std::string("static scratch address: ") + hipGetErrorString(e));
+    return head_logits_into(s, (bf16_t*)buf, x, num_x_rows, rows, num_rows, logits, ld_logits, (hipStream_t)stream);
 }
 
 gllm_status gllm_op_sample(const float* logits, int64_t ld_logits, int32_t num_rows, int32_t vocab,

@@ -8,6 +8,7 @@ from .binding import GLLM_OK, GllmError, _stream_ptr, load_library
 EXPORTS = [
     "gllm_op_embedding", "gllm_head_create", "gllm_head_destroy", "gllm_head_last_error", "gllm_head_workspace_bytes",
     "gllm_head_bind_workspace", "gllm_head_load", "gllm_head_logits", "gllm_head_padded_vocab", "gllm_op_sample",
+    "gllm_head_logits_static", "gllm_head_static_scratch_bytes",
 ]
 
 
@@ -40,6 +41,10 @@ def _lib():
         lib.gllm_head_load.argtypes = [vp, vp, vp, vp]
         lib.gllm_head_logits.restype = i32
         lib.gllm_head_logits.argtypes = [vp, vp, i32, vp, i32, vp, i64, vp]
+        lib.gllm_head_logits_static.restype = i32
+        lib.gllm_head_logits_static.argtypes = [vp, vp, i32, vp, i32, vp, i64, vp]
+        lib.gllm_head_static_scratch_bytes.restype = C.c_size_t
+        lib.gllm_head_static_scratch_bytes.argtypes = []
         lib.gllm_head_padded_vocab.restype = i32
         lib.gllm_head_padded_vocab.argtypes = [vp]
         lib.gllm_op_sample.restype = i32
@@ -64,7 +69,7 @@ def gllm_op_sample(logits, vocab: int, temperature, top_k, top_p, u, out_ids, st
 
 
 class Head:
-    def __init__(self, hidden: int, vocab: int, max_rows: int, rms_eps: float, device="cuda"):
+    def __init__(self, hidden: int, vocab: int, max_rows: int, rms_eps: float, device="cuda", bind_workspace: bool = True):
         import torch
         self.lib = _lib()
         cfg = gllm_head_config(hidden, vocab, max_rows, 0, rms_eps)
@@ -75,8 +80,9 @@ class Head:
         self.handle = h
         self.vocab = vocab
         self.padded_vocab = int(self.lib.gllm_head_padded_vocab(h))
-        self._ws = torch.empty(int(self.lib.gllm_head_workspace_bytes(h)), dtype=torch.uint8, device=device)
-        self._check(self.lib.gllm_head_bind_workspace(h, self._ws.data_ptr(), self._ws.numel()))
+        if bind_workspace:
+            self._ws = torch.empty(int(self.lib.gllm_head_workspace_bytes(h)), dtype=torch.uint8, device=device)
+            self._check(self.lib.gllm_head_bind_workspace(h, self._ws.data_ptr(), self._ws.numel()))
 
     def _check(self, st: int) -> None:
         if st != GLLM_OK:
@@ -97,3 +103,8 @@ class Head:
         """x: fp32 [T, H]; rows: int32 [M] (device); out: fp32 [M, >= padded_vocab]."""
         self._check(self.lib.gllm_head_logits(self.handle, x.data_ptr(), x.shape[0], rows.data_ptr(), rows.shape[0],
                                               out.data_ptr(), out.stride(0), _stream_ptr(stream)))
+
+    def logits_static(self, x, rows, out, stream=None) -> None:
+        """The same through gllm_head_logits_static (scratch inside the library, no workspace needed)."""
+        self._check(self.lib.gllm_head_logits_static(self.handle, x.data_ptr(), x.shape[0], rows.data_ptr(), rows.shape[0],
+                                                     out.data_ptr(), out.stride(0), _stream_ptr(stream)))
