@@ -28,12 +28,35 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 SETUP_PASSES = 8            # untimed passes before the warm-up: first-use costs of every kernel and staging slot
 
-# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command, scaled by a
-# plain 1 GiB copy (profiles/stage_llama3_8b_pp4_hbm_traffic.txt): mean over the GEMM launches of a step,
-# and the decode attention kernel.  Measured offline (counters cannot be read from inside the process).
-MEASURED_TRAFFIC_BYTES = {
-    "llama3_8b_pp4": {"gemm": 476.4e6, "decode_attention": 2467.1e6 + 2.1e6},
-}
+# HBM-side bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very command (counters
+# cannot be read from inside the process), scaled by a plain 1 GiB copy; their summaries are committed as
+# profiles/stage_<config>_hbm_traffic.txt, each ending in a line
+#   bench.py reads: gemm_bytes_per_launch=<float> decode_attention_bytes_per_launch=<float>
+# A configuration without such a file reports traffic = null.
+def measured_traffic(config):
+    path = os.path.join(ROOT, "profiles", f"stage_{config}_hbm_traffic.txt")
+    out = {"source": None}
+    try:
+        text = open(path).read()
+    except OSError:
+        return out
+    import re
+    for key in ("gemm", "decode_attention"):
+        m = re.search(rf"{key}_bytes_per_launch=([0-9.eE+-]+)", text)
+        if m:
+            out[key] = float(m.group(1))
+    out["source"] = f"profiles/stage_{config}_hbm_traffic.txt (offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command, copy-calibrated)"
+    return out
+
+
+def cpu_model():
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def prefill_attn_flops(shape, batch):
@@ -114,19 +137,27 @@ def main():
     out = torch.empty(T, shape.hidden, dtype=torch.bfloat16, device=dev)
     torch.cuda.synchronize()
 
-    # sample for the CPU baseline, taken before the forward touches the pool
+    # sample for the CPU baseline, taken before the forward touches the pool: more than 64 rows, so that the oracle's
+    # many-rows loop nest is what is timed; if the stage is too deep for about 20 s of CPU work the oracle runs its
+    # first layers only (stated in the output)
     sample = None
+    cpu_layers = shape.num_layers
     if not args.no_cpu_baseline:
-        dec = [i for i in range(batch.num_seqs) if batch.new_tokens[i] == 1][:8]
+        dec = [i for i in range(batch.num_seqs) if batch.new_tokens[i] == 1][:24]
         pre = [i for i in range(batch.num_seqs) if batch.new_tokens[i] > 1][:1]
         ids = pre + dec
-        nt = [min(int(batch.new_tokens[i]), 40) for i in pre] + [1] * len(dec)
+        nt = [min(int(batch.new_tokens[i]), 72 - len(dec)) for i in pre] + [1] * len(dec)
+        if sum(nt) < 65:            # a decode-only batch: more decode rows
+            dec = [i for i in range(batch.num_seqs) if batch.new_tokens[i] == 1][:72]
+            ids, nt = pre + dec, nt[:len(pre)] + [1] * len(dec)
         sub, kp, vp, _ = synth.compact_subset(shape, batch, ids, nt, k_pool, v_pool)
         rows = []
         offs = batch.row_offsets
         for i, n in zip(ids, nt):
             rows += list(range(int(offs[i]), int(offs[i]) + n))
         sample = (sub, kp, vp, synth.bf16_bits(hidden[rows]))
+        work_per_layer = sub.num_tokens * shape.gemm_flop_per_token_layer        # flop; the GEMMs dominate
+        cpu_layers = max(1, min(shape.num_layers, int(6.0e11 // work_per_layer)))
 
     def step():
         stage.forward(batch.new_tokens, batch.cached_len, batch.block_tables, hidden, out)
@@ -152,6 +183,14 @@ def main():
     gemm_flop_step = T * shape.gemm_flop_per_token_layer * L
     roofline = None
     extra = {}
+    traffic = measured_traffic(args.config)
+    # operands once + result once, averaged over the four projections of a layer (result: fp32 planes for QKV, O and
+    # down as planned for this row count, bf16 for gate/up)
+    H_, I_, NQ, QD = shape.hidden, shape.intermediate, shape.n_qkv, shape.q_dim
+    def _planes(n, k):
+        return binding.gllm_op_gemm_plan(T, (n + 255) // 256 * 256, k, 0, 8)[1]
+    alg_gemm_bytes = ((T * H_ * 2 + NQ * H_ * 2 + _planes(NQ, H_) * T * NQ * 4) + (T * QD * 2 + H_ * QD * 2 + _planes(H_, QD) * T * H_ * 4)
+                      + (T * H_ * 2 + 2 * I_ * H_ * 2 + T * I_ * 2) + (T * I_ * 2 + H_ * I_ * 2 + _planes(H_, (I_ + 127) // 128 * 128) * T * H_ * 4)) / 4.0
     if not args.no_profile_pass:
         stage.set_profiling(True)
         for _ in range(args.steps):
@@ -166,8 +205,10 @@ def main():
         achieved = gemm_flop_step / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
         roofline = {"kernel": "gemm_bf16_kernel", "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get("gemm") if args.layers == 0 else None,
+                    "traffic": traffic.get("gemm") if args.layers == 0 else None,
                     "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated; includes Infinity Cache hits)",
+                    "traffic_source": traffic["source"],
+                    "algorithmic_bytes_per_launch": alg_gemm_bytes,
                     "launches_per_step": gemm_launches,
                     "avg_launch_ms": round(gemm_ms / max(gemm_launches, 1), 5),
                     "flop_per_launch": gemm_flop_step / max(gemm_launches, 1)}
@@ -182,7 +223,7 @@ def main():
             extra["roofline_decode_attention"] = {
                 "kernel": "decode_attention_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config, {}).get("decode_attention") if args.layers == 0 else None,
+                "traffic": traffic.get("decode_attention") if args.layers == 0 else None,
                 "avg_launch_ms": round(per_step["attn_decode"] / L, 5), "bytes_per_launch": kvb}
         pf = prefill_attn_flops(shape, batch)
         if per_step.get("attn_prefill", 0) > 0:
@@ -214,13 +255,19 @@ def main():
         import oracle
         sub, kp, vp, xs = sample
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        import dataclasses as _dc
+        cpu_shape = _dc.replace(shape, num_layers=cpu_layers)
+        per_layer = synth.pool_elems_per_layer(shape, sub.num_blocks)
         t0 = time.perf_counter()
-        oracle.stage_forward(shape, host_weights, sub.new_tokens, sub.cached_len, sub.block_tables,
-                             sub.num_blocks, kp, vp, xs)
+        oracle.stage_forward(cpu_shape, host_weights[:cpu_layers], sub.new_tokens, sub.cached_len, sub.block_tables,
+                             sub.num_blocks, kp[:cpu_layers * per_layer], vp[:cpu_layers * per_layer], xs)
         dt = time.perf_counter() - t0
-        cpu = {"value": round(sub.num_tokens / dt, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
-               "sample": f"{sub.num_tokens} token rows of the same batch ({int((sub.new_tokens > 1).sum())} prefill-chunk "
-                         f"prefix, {int((sub.new_tokens == 1).sum())} decode rows), all {L} layers, {dt:.1f} s"}
+        # tokens/s of the whole stage: rows per second through one layer, divided by the stage's layer count
+        cpu = {"value": round(sub.num_tokens * cpu_layers / dt / L, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+               "cpu_model": cpu_model(),
+               "sample": f"{sub.num_tokens} token rows of the same batch ({int(sub.new_tokens[sub.new_tokens > 1].sum())} leading rows of a prefill "
+                         f"chunk, {int((sub.new_tokens == 1).sum())} decode rows), {cpu_layers} of the {L} layers"
+                         f"{'' if cpu_layers == L else ' (scaled to the whole stage)'}, {dt:.1f} s"}
 
     line = {
         "metric": "stage tokens/sec on mixed prefill+decode batch",

@@ -453,5 +453,5 @@ def test_row_mixed_option_belongs_to_one_stage():
     out_b = b.run(batch, to_dev_bits(kp0), to_dev_bits(vp0), x)[1]
     out_a = a.run(batch, to_dev_bits(kp0), to_dev_bits(vp0), x)[1]
     assert torch.equal(out_a, ref_a)                                    # a's plan is unchanged
-    assert torch.allclose(out_a, out_b, rtol=0, atol=1e-4)              # same result either way (tile shapes differ)
+    assert torch.allclose(out_a, out_b, rtol=0, atol=5e-3)              # same result either way (tile shapes and split counts may differ)
     a.stage.destroy(); b.stage.destroy()
