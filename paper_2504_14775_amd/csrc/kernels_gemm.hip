@@ -36,13 +36,23 @@ __device__ __forceinline__ float silu(float z) {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// The work of one workgroup: output tile number `wg_linear` of a tiles_m x tiles_n grid of BM x BN tiles
-// whose first column is n_base and whose first row is m_base.
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn; this turns id `wg` of `count` into a work number such
+// that every XCD receives one contiguous range of work numbers (XCD x gets workgroups x, x+8, ...: count / 8 of them,
+// one more for x < count % 8).
+__device__ __forceinline__ int xcd_contiguous(int wg, int count) {
+    const int q = count >> 3, rem = count & 7;
+    const int xcd = wg & 7, idx = wg >> 3;
+    return xcd * q + min(xcd, rem) + idx;
+}
+
+// The work of one workgroup: output tile number `tile_idx` (in XCD-contiguous numbering, see above) of a tiles_m x
+// tiles_n grid of BM x BN tiles whose first column is n_base and whose first row is m_base, k-share `split` of
+// `num_splits` (each share has its own output plane).
 // NS LDS stages of 64 k-values each (NS = 2 fills LDS for the 256x256 tile).
 template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
                                           int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
-                                          int tiles_m, int tiles_n, int n_base, int wg_linear,
+                                          int tiles_m, int tiles_n, int n_base, int tile_idx, int split, int num_splits,
                                           int64_t split_stride, int m_base = 0) {
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
@@ -54,15 +64,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     static_assert(MODE != GEMM_SWIGLU_BF16 || TN % 2 == 0, "SwiGLU needs gate and up blocks in one wave");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    // ---- tile assignment (XCD aware) ----
-    const int num_tiles = tiles_m * tiles_n;
-    int wg = wg_linear;
-    {
-        // XCD x receives workgroups x, x+8, ...: q of them, one more for x < rem
-        const int q = num_tiles >> 3, rem = num_tiles & 7;
-        const int xcd = wg & 7, idx = wg >> 3;
-        wg = xcd * q + min(xcd, rem) + idx;
-    }
+    // ---- tile assignment: tiles are numbered band by band ----
+    const int wg = tile_idx;
     constexpr int BAND = 8;  // tile columns per band
     const int band = wg / (BAND * tiles_m);
     const int band_cols = min(BAND, tiles_n - band * BAND);
@@ -75,10 +78,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // split-K: blockIdx.y owns a contiguous share of the k range and its own output plane
-    const int KT = (K / BK) / (int)gridDim.y;
-    const int kt_base = blockIdx.y * KT;
-    const int64_t split_off = (int64_t)blockIdx.y * split_stride;
+    // split-K: a share is a contiguous part of the k range with its own output plane
+    const int KT = (K / BK) / num_splits;
+    const int kt_base = split * KT;
+    const int64_t split_off = (int64_t)split * split_stride;
 
     // ---- loader: wave w fills groups w, w + NW, ...; lane offsets are the same for every group ----
     // group g covers rows 8g .. 8g+7 = lines 4g .. 4g+3; NW is even, so g has the parity of `wave`
@@ -270,7 +273,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
                                                                     void* __restrict__ out, int64_t ldc, int M,
                                                                     int K, int tiles_m, int tiles_n,
                                                                     int64_t split_stride) {
-    gemm_tile<BM, BN, WGM, WGN, MODE, NS>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, blockIdx.x, split_stride);
+    // Split-K launches are a (tiles, splits) grid; workgroup ids run over the tiles first.  All of it is renumbered at
+    // once, k-share by k-share, so that an XCD works on tiles of ONE k-share at a time where it can: the tiles that
+    // share its L2 then read the same k range of their A and W panels (with both shares of a tile range on one XCD,
+    // as the plain per-share numbering would place them, the L2 sees half as many tiles per panel).
+    const int num_tiles = tiles_m * tiles_n;
+    const int v = xcd_contiguous(blockIdx.x + blockIdx.y * num_tiles, num_tiles * (int)gridDim.y);
+    gemm_tile<BM, BN, WGM, WGN, MODE, NS>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, v % num_tiles, v / num_tiles,
+                                          gridDim.y, split_stride);
 }
 
 // Two tile shapes in one launch: the first big_tiles workgroups cover columns [0, n_split) with 256x256
@@ -283,10 +293,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_mixed_kernel(const bf16_t* __re
                                                                int tiles_m, int big_cols, int small_cols) {
     const int big_tiles = tiles_m * big_cols;
     if ((int)blockIdx.x < big_tiles)
-        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, big_cols, 0, blockIdx.x, 0);
+        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, big_cols, 0,
+                                        xcd_contiguous(blockIdx.x, big_tiles), 0, 1, 0);
     else
         gemm_tile<256, 128, 4, 2, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, small_cols, big_cols * 256,
-                                        blockIdx.x - big_tiles, 0);
+                                        xcd_contiguous(blockIdx.x - big_tiles, tiles_m * small_cols), 0, 1, 0);
 }
 
 // Two tile heights in one launch: the first big_tiles workgroups cover the whole bands of 256 rows with 256x256
@@ -299,9 +310,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_rowmix_kernel(const bf16_t* __r
                                                                 int bands, int tiles_n, int64_t split_stride) {
     const int big_tiles = bands * tiles_n;
     if ((int)blockIdx.x < big_tiles)
-        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, bands, tiles_n, 0, blockIdx.x, split_stride);
+        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, bands, tiles_n, 0, xcd_contiguous(blockIdx.x, big_tiles),
+                                        blockIdx.y, gridDim.y, split_stride);
     else
-        gemm_tile<BMR, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, 1, tiles_n, 0, blockIdx.x - big_tiles, split_stride,
+        gemm_tile<BMR, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, 1, tiles_n, 0,
+                                        xcd_contiguous(blockIdx.x - big_tiles, tiles_n), blockIdx.y, gridDim.y, split_stride,
                                         bands * 256);
 }
 
