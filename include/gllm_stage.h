@@ -199,7 +199,9 @@ const char* gllm_profile_class_name(int32_t i);
  * of the weight stream in flight), 8 = 256x256 tiles for the whole bands of 256 rows plus 64x256 or 128x256 tiles
  * for a last band of at most 128 rows (only for m > 256 with 0 < m mod 256 <= 128 and n a multiple of 256), 9 = 288x192
  * (six wavefronts; only for 256 < m <= 288, n a multiple of 192, not for SwiGLU: all rows in one band, so the weights
- * are read once); a forced tile that does not fit the shape gives GLLM_E_UNSUPPORTED. */
+ * are read once), 10 / 11 / 12 = tiles 3 / 4 / 8 with a third LDS stage for the weight tile (all 160 KiB of LDS: the
+ * weight loads get two k-steps to land; picked for long k and for few rows); a forced tile that does not fit the
+ * shape gives GLLM_E_UNSUPPORTED. */
 gllm_status gllm_op_gemm_bf16(const void* a, int64_t lda, const void* w, int64_t ldw, void* out, int64_t ldc,
                               int32_t m, int32_t n, int32_t k, int32_t mode, int32_t tile, void* stream);
 

@@ -36,7 +36,7 @@ enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 // 4 forces the mixed 256x256 + 256x128 launch (only where gemm_mixed_rem_cols(m, n) > 0); 5 = 256x192 (not SwiGLU);
 // 6 = 128x128 with four LDS stages; 7 = 64x128 with three LDS stages (up to 64 rows per tile row: weight streaming);
 // 8 = 256x256 tiles for the whole bands of 256 rows plus 64x256 or 128x256 tiles for a last band of at most 128 rows
-// (only where gemm_rowmix_rem_rows(m, n) > 0).
+// (only where gemm_rowmix_rem_rows(m, n) > 0); 9 = 288x192; 10, 11, 12 = tiles 3, 4, 8 with a third LDS stage for the W tile.
 // splits > 1 (store mode only): split s covers k range [s*k/splits, (s+1)*k/splits) and writes its partial
 // product to out + s*split_stride floats; the consumer sums the planes in order.
 hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc,

@@ -48,8 +48,11 @@ __device__ __forceinline__ int xcd_contiguous(int wg, int count) {
 // The work of one workgroup: output tile number `tile_idx` (in XCD-contiguous numbering, see above) of a tiles_m x
 // tiles_n grid of BM x BN tiles whose first column is n_base and whose first row is m_base, k-share `split` of
 // `num_splits` (each share has its own output plane).
-// NS LDS stages of 64 k-values each (NS = 2 fills LDS for the 256x256 tile).
-template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
+// NS LDS stages of 64 k-values for the A tile and NSW (NS or NS + 1) for the W tile.  The weights stream from HBM,
+// the activations are re-read from the caches by every tile column, so where LDS cannot hold one more stage of both
+// (256x256: two of each fill 128 of the 160 KiB) the W tile alone gets the third: its loads then have two k-steps
+// to land instead of one.
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
                                           int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
                                           int tiles_m, int tiles_n, int n_base, int tile_idx, int split, int num_splits,
@@ -57,10 +60,12 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
-    constexpr int GROUPS = (BM + BN) / 8;          // 1 KiB load groups per stage
-    constexpr int GPW = GROUPS / NW;               // groups per wave
-    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-    static_assert(GROUPS % NW == 0 && NW % 2 == 0, "load groups must divide among an even number of waves");
+    constexpr int GA = BM / 8 / NW, GW = BN / 8 / NW;  // 1 KiB load groups per wave and stage: A, W
+    constexpr int GPW = GA + GW;
+    constexpr int A_STAGE = BM * BK * 2, W_STAGE = BN * BK * 2, W_BASE = NS * A_STAGE;
+    constexpr int LDS_BYTES = NS * A_STAGE + NSW * W_STAGE;
+    static_assert(NSW == NS || NSW == NS + 1, "the W tile has as many stages as the A tile, or one more");
+    static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0 && NW % 2 == 0, "load groups must divide among an even number of waves");
     static_assert(MODE != GEMM_SWIGLU_BF16 || TN % 2 == 0, "SwiGLU needs gate and up blocks in one wave");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -92,16 +97,23 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     const uint32_t voff_w = (uint32_t)(lrow * ldw + lgrp * 8) * 2u;
     const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
     const char* w_tile = reinterpret_cast<const char*>(W + (int64_t)n0 * ldw);
-    static_assert((BM / 8) % NW == 0, "A and W load groups must not mix within one unrolled step");
-    auto issue_loads = [&](int kt, int stage) {
-        unsigned char* sbase = smem + stage * STAGE_BYTES;
+    // tile kt of A into A stage `stage` / of W into W stage `stage` (wave w fills groups w, w + NW, ...)
+    auto issue_a = [&](int kt, int stage) {
+        unsigned char* sbase = smem + stage * A_STAGE;
         const int64_t kbyte = (int64_t)(kt + kt_base) * (BK * 2);
 #pragma unroll
-        for (int i = 0; i < GPW; ++i) {
-            const int g = wave + i * NW;  // wave-uniform; A groups come first
-            const char* src = (i * NW < BM / 8) ? a_tile + (int64_t)(g * 8) * lda * 2 + kbyte + voff_a
-                                                : w_tile + (int64_t)(g * 8 - BM) * ldw * 2 + kbyte + voff_w;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(sbase + g * 1024), 16, 0, 0);
+        for (int i = 0; i < GA; ++i) {
+            const int g = wave + i * NW;  // wave-uniform
+            __builtin_amdgcn_global_load_lds((gptr_t)(a_tile + (int64_t)(g * 8) * lda * 2 + kbyte + voff_a), (lptr_t)(sbase + g * 1024), 16, 0, 0);
+        }
+    };
+    auto issue_w = [&](int kt, int stage) {
+        unsigned char* sbase = smem + W_BASE + stage * W_STAGE;
+        const int64_t kbyte = (int64_t)(kt + kt_base) * (BK * 2);
+#pragma unroll
+        for (int i = 0; i < GW; ++i) {
+            const int g = wave + i * NW;
+            __builtin_amdgcn_global_load_lds((gptr_t)(w_tile + (int64_t)(g * 8) * ldw * 2 + kbyte + voff_w), (lptr_t)(sbase + g * 1024), 16, 0, 0);
         }
     };
 
@@ -129,10 +141,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     {
         const int fsw = (frow >> 1) & 7, fpar = (frow & 1) * 8;
         const int a_off = (wm * WTM + (frow & ~1)) * (BK * 2);
-        const int w_off = (BM + wn * WTN + (frow & ~1)) * (BK * 2);
-        auto load_frags = [&](int stage, int kk, int buf) {
-            const unsigned char* sa = smem + stage * STAGE_BYTES + a_off;
-            const unsigned char* sw = smem + stage * STAGE_BYTES + w_off;
+        const int w_off = W_BASE + (wn * WTN + (frow & ~1)) * (BK * 2);
+        auto load_frags = [&](int kt, int kk, int buf) {  // fragments of k-step kk of tile kt
+            const unsigned char* sa = smem + (kt % NS) * A_STAGE + a_off;
+            const unsigned char* sw = smem + (kt % NSW) * W_STAGE + w_off;
             const int g = ((fpar + kk * 2 + fgrp) ^ fsw) * 16;
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * (BK * 2) + g);
@@ -163,44 +175,48 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
             }
         };
 
-        // Software pipeline.  Global: tiles kt+1 .. kt+NS-1 are in flight while tile kt is multiplied (NS = 2
-        // for the large tiles, which fill LDS; more stages for the small tile when the operands stream from
-        // HBM).  LDS -> registers: the fragments of k-step kk+1 are fetched while k-step kk is multiplied, also
-        // across the tile boundary: the barrier sits before the last k-step of a tile, after which the next
-        // tile's first fragments are fetched under the MFMAs of that last k-step.  Loads past the last tile
-        // re-read it into a stage nobody reads again, so every iteration issues the same number of loads and
-        // the wait counts are compile-time constants.
+        // Software pipeline.  Global: tiles kt+1 .. kt+NS-1 of A (.. kt+NSW-1 of W) are in flight while tile kt is
+        // multiplied.  LDS -> registers: the fragments of k-step kk+1 are fetched while k-step kk is multiplied, also
+        // across the tile boundary: the barrier sits before the last k-step of a tile, after which the next tile's
+        // first fragments are fetched under the MFMAs of that last k-step.  Loads past the last tile re-read it into
+        // a stage nobody reads again, so every iteration issues the same number of loads and the wait counts are
+        // compile-time constants.  Loads complete in issue order: each step issues its A tile before its W tile, so
+        // "all but the newest ..." leaves exactly the tiles that may still be in flight.
         constexpr int KK = BK / 16;
-        static_assert((NS - 1) * GPW < 64, "outstanding loads must fit the vmcnt field");
+        constexpr int kInFlight = (NS - 2) * GPW + (NSW - NS) * GW;  // loads that may be outstanding at a step's barrier
+        static_assert(kInFlight + GPW < 64, "outstanding loads must fit the vmcnt field");
 #pragma unroll
-        for (int i = 0; i < NS; ++i) issue_loads(min(i, KT - 1), i);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * GPW) : "memory");
+        for (int i = 0; i < NS; ++i) {
+            issue_a(min(i, KT - 1), i);
+            issue_w(min(i, KT - 1), i);
+        }
+        if (NSW > NS) issue_w(min(NS, KT - 1), NS);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * GPW + (NSW - NS) * GW) : "memory");
         __builtin_amdgcn_s_barrier();
         load_frags(0, 0, 0);
         for (int kt = 0; kt < KT - 1; ++kt) {
-            const int stage = kt % NS;
 #pragma unroll
             for (int kk = 0; kk < KK - 1; ++kk) {
-                load_frags(stage, kk + 1, (kk + 1) & 1);
+                load_frags(kt, kk + 1, (kk + 1) & 1);
                 mfmas(kk & 1);
                 interleave();
             }
-            // tile kt+1 must have landed (tiles kt+2 .. kt+NS-1 may still be in flight) and this wave's last
-            // fragments of tile kt must be in registers before anybody overwrites the stage
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * GPW) : "memory");
+            // tile kt+1 must have landed (later tiles may still be in flight) and this wave's last fragments of
+            // tile kt must be in registers before anybody overwrites its stages
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kInFlight) : "memory");
             __builtin_amdgcn_s_barrier();
-            // branch-free tail (one scheduling region): the loads of tile kt+NS into the stage just vacated,
-            // the first fragments of tile kt+1, the last MFMAs of tile kt
-            issue_loads(min(kt + NS, KT - 1), stage);
-            load_frags((kt + 1) % NS, 0, KK & 1);
+            // branch-free tail (one scheduling region): the loads into the stages just vacated, the first fragments
+            // of tile kt+1, the last MFMAs of tile kt
+            issue_a(min(kt + NS, KT - 1), kt % NS);
+            issue_w(min(kt + NSW, KT - 1), kt % NSW);
+            load_frags(kt + 1, 0, KK & 1);
             mfmas((KK - 1) & 1);
             interleave_with_loads();
         }
         {
-            const int stage = (KT - 1) % NS;
 #pragma unroll
             for (int kk = 0; kk < KK - 1; ++kk) {
-                load_frags(stage, kk + 1, (kk + 1) & 1);
+                load_frags(KT - 1, kk + 1, (kk + 1) & 1);
                 mfmas(kk & 1);
                 interleave();
             }
@@ -217,7 +233,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     constexpr int LPR = C / 4;                                      // lanes per row on the way out
     constexpr int RPI = 64 / LPR;                                   // rows per read instruction (lanes >= RPI*LPR idle)
     static_assert(32 % RPI == 0, "a slab must be a whole number of read instructions");
-    static_assert(NW * 32 * CS * 4 <= NS * STAGE_BYTES, "epilogue slab must fit in the tile buffers");
+    static_assert(NW * 32 * CS * 4 <= LDS_BYTES, "epilogue slab must fit in the tile buffers");
     float* slab = reinterpret_cast<float*>(smem) + wave * (32 * CS);
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
     const int orow = lane / LPR, ocol = (lane % LPR) * 4;
@@ -267,7 +283,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ W, int64_t ldw,
                                                                     void* __restrict__ out, int64_t ldc, int M,
@@ -279,52 +295,52 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     // as the plain per-share numbering would place them, the L2 sees half as many tiles per panel).
     const int num_tiles = tiles_m * tiles_n;
     const int v = xcd_contiguous(blockIdx.x + blockIdx.y * num_tiles, num_tiles * (int)gridDim.y);
-    gemm_tile<BM, BN, WGM, WGN, MODE, NS>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, v % num_tiles, v / num_tiles,
+    gemm_tile<BM, BN, WGM, WGN, MODE, NS, NSW>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, v % num_tiles, v / num_tiles,
                                           gridDim.y, split_stride);
 }
 
 // Two tile shapes in one launch: the first big_tiles workgroups cover columns [0, n_split) with 256x256
 // tiles (whole rounds of the 256 compute units), the rest cover [n_split, N) with 256x128 tiles, so that
 // the last, partial round still gives every compute unit a (half-size) tile.  8 waves either way.
-template <int MODE>
+template <int MODE, int NSW>
 __global__ __launch_bounds__(512) void gemm_bf16_mixed_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                const bf16_t* __restrict__ W, int64_t ldw,
                                                                void* __restrict__ out, int64_t ldc, int M, int K,
                                                                int tiles_m, int big_cols, int small_cols) {
     const int big_tiles = tiles_m * big_cols;
     if ((int)blockIdx.x < big_tiles)
-        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, big_cols, 0,
-                                        xcd_contiguous(blockIdx.x, big_tiles), 0, 1, 0);
+        gemm_tile<256, 256, 2, 4, MODE, 2, NSW>(A, lda, W, ldw, out, ldc, M, K, tiles_m, big_cols, 0,
+                                                xcd_contiguous(blockIdx.x, big_tiles), 0, 1, 0);
     else
-        gemm_tile<256, 128, 4, 2, MODE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, small_cols, big_cols * 256,
-                                        xcd_contiguous(blockIdx.x - big_tiles, tiles_m * small_cols), 0, 1, 0);
+        gemm_tile<256, 128, 4, 2, MODE, 2, NSW>(A, lda, W, ldw, out, ldc, M, K, tiles_m, small_cols, big_cols * 256,
+                                                xcd_contiguous(blockIdx.x - big_tiles, tiles_m * small_cols), 0, 1, 0);
 }
 
 // Two tile heights in one launch: the first big_tiles workgroups cover the whole bands of 256 rows with 256x256
 // tiles, the rest cover the last band -- at most BMR rows are left -- with BMR x 256 tiles, so a row count just above a
 // multiple of 256 does not pay for a whole band of padding.  8 waves either way; blockIdx.y is the split-K share.
-template <int MODE, int BMR>
+template <int MODE, int BMR, int NSW>
 __global__ __launch_bounds__(512) void gemm_bf16_rowmix_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                 const bf16_t* __restrict__ W, int64_t ldw,
                                                                 void* __restrict__ out, int64_t ldc, int M, int K,
                                                                 int bands, int tiles_n, int64_t split_stride) {
     const int big_tiles = bands * tiles_n;
     if ((int)blockIdx.x < big_tiles)
-        gemm_tile<256, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, bands, tiles_n, 0, xcd_contiguous(blockIdx.x, big_tiles),
-                                        blockIdx.y, gridDim.y, split_stride);
+        gemm_tile<256, 256, 2, 4, MODE, 2, NSW>(A, lda, W, ldw, out, ldc, M, K, bands, tiles_n, 0,
+                                                xcd_contiguous(blockIdx.x, big_tiles), blockIdx.y, gridDim.y, split_stride);
     else
-        gemm_tile<BMR, 256, 2, 4, MODE>(A, lda, W, ldw, out, ldc, M, K, 1, tiles_n, 0,
-                                        xcd_contiguous(blockIdx.x - big_tiles, tiles_n), blockIdx.y, gridDim.y, split_stride,
-                                        bands * 256);
+        gemm_tile<BMR, 256, 2, 4, MODE, 2, NSW>(A, lda, W, ldw, out, ldc, M, K, 1, tiles_n, 0,
+                                                xcd_contiguous(blockIdx.x - big_tiles, tiles_n), blockIdx.y, gridDim.y,
+                                                split_stride, bands * 256);
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
 hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                        int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
     if (n % BN != 0) return hipErrorInvalidValue;
     const int tiles_m = (int)ceil_div(m, BM), tiles_n = n / BN;
-    const size_t smem = NS * (BM + BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, NS>;
+    const size_t smem = (NS * BM + NSW * BN) * BK * sizeof(bf16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, NS, NSW>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -346,6 +362,7 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
         case 1: return launch_tile<256, 128, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 2: return launch_tile<256, 256, 2, 2, MODE>(GLLM_TILE_ARGS);
         case 3: return launch_tile<256, 256, 2, 4, MODE>(GLLM_TILE_ARGS);
+        case 10: return launch_tile<256, 256, 2, 4, MODE, 2, 3>(GLLM_TILE_ARGS);  // third LDS stage for the W tile: all 160 KiB
         case 6: return launch_tile<128, 128, 2, 2, MODE, 4>(GLLM_TILE_ARGS);
         case 7: return launch_tile<64, 128, 2, 2, MODE, 3>(GLLM_TILE_ARGS);
         case 9:  // one 288-row tile covers all rows; it reads 288 of them, which the row padding (to 256) covers above 256
@@ -363,12 +380,12 @@ hipError_t launch_mode(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
 
 // Mixed launch (see gemm_bf16_mixed_kernel); rem_cols 256-wide tile columns are turned into 2*rem_cols
 // 128-wide ones.
-template <int MODE>
+template <int MODE, int NSW>
 hipError_t launch_mixed(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                         int n, int k, int rem_cols, hipStream_t stream) {
     const int tiles_m = (int)ceil_div(m, 256), big_cols = n / 256 - rem_cols, small_cols = 2 * rem_cols;
-    const size_t smem = 2 * (256 + 256) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_mixed_kernel<MODE>;
+    const size_t smem = (2 * 256 + NSW * 256) * BK * sizeof(bf16_t);
+    auto kern = gemm_bf16_mixed_kernel<MODE, NSW>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -382,15 +399,15 @@ hipError_t launch_mixed(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t l
 }
 
 // Row-mixed launch (see gemm_bf16_rowmix_kernel); rem_rows is 64 or 128.
-template <int MODE>
+template <int MODE, int NSW>
 hipError_t launch_rowmix(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
                          int n, int k, int rem_rows, int splits, int64_t split_stride, hipStream_t stream) {
     const int bands = m / 256, tiles_n = n / 256;
-    const size_t smem = 2 * (256 + 256) * BK * sizeof(bf16_t);
+    const size_t smem = (2 * 256 + NSW * 256) * BK * sizeof(bf16_t);
     const dim3 grid((bands + 1) * tiles_n, splits);
 #define GLLM_ROWMIX(R)                                                                                             \
     do {                                                                                                           \
-        auto kern = gemm_bf16_rowmix_kernel<MODE, R>;                                                              \
+        auto kern = gemm_bf16_rowmix_kernel<MODE, R, NSW>;                                                           \
         static bool configured = false;                                                                            \
         if (!configured) {                                                                                         \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                \
@@ -503,6 +520,14 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits, bool row_mixed
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{7, s}; }
         }
     }
+    // The 256x256 tile shapes exist with a third LDS stage for the W tile (ids 10, 11, 12 for 3, 4, 8): two k-steps for the
+    // weight loads to land instead of one.  Measured against the two-stage forms on the four stage shapes (weights cold):
+    // +3..5 % where a tile walks 80 or more k-steps (hidden >= 5120; the down projection), +15..20 % at 512 rows and
+    // below, where the product is bound by the weight stream; even or -2 % on short k with many rows (hidden 4096 at
+    // 2048 rows), where the loads land in time anyway.
+    const int steps = its / best.splits;
+    if ((best.tile == 3 || best.tile == 4 || best.tile == 8) && (steps >= 80 || m <= 1024))
+        best.tile = best.tile == 3 ? 10 : best.tile == 4 ? 11 : 12;
     return best;
 }
 
@@ -523,28 +548,36 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
             const double c3 = n % 256 == 0 ? (double)ceil_div(t3, 256) * (steps + 6.0) : 1e30;
             const double c0 = (double)(t0 / 512) * (steps * 0.70 + 2.3) +
                               (t0 % 512 > 256 ? steps * 0.70 + 2.3 : t0 % 512 > 0 ? steps * 0.49 + 2.3 : 0.0);
-            tile = m <= 64 ? 7 : c3 <= c0 ? 3 : (m <= 256 && t0 <= 256) ? 6 : 0;
+            tile = m <= 64 ? 7 : c3 <= c0 ? ((steps >= 80 || m <= 1024) ? 10 : 3) : (m <= 256 && t0 <= 256) ? 6 : 0;
         }
     }
-    if (tile == 8) {  // 256x256 tiles plus a last band of 64 or 128 rows
+    if (tile == 8 || tile == 12) {  // 256x256 tiles plus a last band of 64 or 128 rows (12: third W stage)
         const int rem_rows = gemm_rowmix_rem_rows(m, n);
         if (rem_rows == 0) return hipErrorInvalidValue;
+#define GLLM_ROWMIX_MODE(MODE_)                                                                                              \
+    (tile == 8 ? launch_rowmix<MODE_, 2>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream)          \
+               : launch_rowmix<MODE_, 3>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream))
         switch (mode) {
-            case GEMM_STORE_F32: return launch_rowmix<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream);
-            case GEMM_ADD_F32: return launch_rowmix<GEMM_ADD_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream);
-            case GEMM_SWIGLU_BF16: return launch_rowmix<GEMM_SWIGLU_BF16>(a, lda, w, ldw, out, ldc, m, n, k, rem_rows, splits, split_stride, stream);
+            case GEMM_STORE_F32: return GLLM_ROWMIX_MODE(GEMM_STORE_F32);
+            case GEMM_ADD_F32: return GLLM_ROWMIX_MODE(GEMM_ADD_F32);
+            case GEMM_SWIGLU_BF16: return GLLM_ROWMIX_MODE(GEMM_SWIGLU_BF16);
             default: return hipErrorInvalidValue;
         }
+#undef GLLM_ROWMIX_MODE
     }
-    if (tile == 4) {  // mixed 256x256 / 256x128 launch
+    if (tile == 4 || tile == 11) {  // mixed 256x256 / 256x128 launch (11: third W stage)
         const int rem_cols = gemm_mixed_rem_cols(m, n);
         if (rem_cols == 0 || splits != 1) return hipErrorInvalidValue;
+#define GLLM_MIXED_MODE(MODE_)                                                                    \
+    (tile == 4 ? launch_mixed<MODE_, 2>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream)      \
+               : launch_mixed<MODE_, 3>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream))
         switch (mode) {
-            case GEMM_STORE_F32: return launch_mixed<GEMM_STORE_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream);
-            case GEMM_ADD_F32: return launch_mixed<GEMM_ADD_F32>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream);
-            case GEMM_SWIGLU_BF16: return launch_mixed<GEMM_SWIGLU_BF16>(a, lda, w, ldw, out, ldc, m, n, k, rem_cols, stream);
+            case GEMM_STORE_F32: return GLLM_MIXED_MODE(GEMM_STORE_F32);
+            case GEMM_ADD_F32: return GLLM_MIXED_MODE(GEMM_ADD_F32);
+            case GEMM_SWIGLU_BF16: return GLLM_MIXED_MODE(GEMM_SWIGLU_BF16);
             default: return hipErrorInvalidValue;
         }
+#undef GLLM_MIXED_MODE
     }
     switch (mode) {
         case GEMM_STORE_F32:

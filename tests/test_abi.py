@@ -64,7 +64,7 @@ def test_gemm_planner_choices_are_launchable():
     """Host logic of the tile / split-K planner: whatever it picks must satisfy the launch rules of that tile
     (column multiple, split divides the 64-wide k-steps, splits only in store mode), for the stage shapes and a
     sweep of ragged row counts."""
-    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128, 7: 128, 8: 256, 9: 192}
+    col_multiple = {0: 128, 1: 128, 2: 256, 3: 256, 4: 256, 5: 192, 6: 128, 7: 128, 8: 256, 9: 192, 10: 256, 11: 256, 12: 256}
     seen = set()
     for shape in synth.SHAPES.values():
         H, I = shape.hidden, shape.intermediate
@@ -82,18 +82,23 @@ def test_gemm_planner_choices_are_launchable():
                     assert splits == 1 and tile != 5
                 if tile == 7:
                     assert m <= 64
-                if tile == 8:
+                if tile in (8, 12):
                     assert m > 256 and 0 < m % 256 <= 128
                 if tile == 9:
                     assert 256 < m <= 288 and mode == 0
-                if tile == 4:
+                if tile in (10, 11, 12):      # the third weight stage: long k or few rows
+                    assert (k // 64) // splits >= 80 or m <= 1024
+                if tile in (4, 11):
                     tiles = ((m + 255) // 256) * (n // 256)
                     assert splits == 1 and tiles >= 256 and 0 < tiles % 256 <= 128
                 assert B.gllm_op_gemm_plan(m, n, k, mode, 8) == (tile, splits)          # deterministic
                 assert B.gllm_op_gemm_plan(m, n, k, mode, 1)[1] == 1                    # the cap is respected
-    assert {3, 6, 7, 8}.issubset(seen)   # big problems get 256x256 tiles (with a short last band where rows are left over), few rows the deep 128x128 or the 64x128 one
+    # big problems get 256x256 tiles (with a short last band where rows are left over; with a third weight stage for
+    # long k or few rows), few rows the deep 128x128 or the 64x128 one
+    assert {3, 6, 7, 8, 10, 12}.issubset(seen), seen
     # the vocabulary projection of a micro-batch of 256 decode rows plus one chunk end: one 288-row band
     assert B.gllm_op_gemm_plan(257, 128256, 4096, 0, 1) == (9, 1)
-    assert B.gllm_op_gemm_plan(256, 128256, 4096, 0, 1)[0] == 3 and B.gllm_op_gemm_plan(289, 128256, 4096, 0, 1)[0] == 8
+    assert B.gllm_op_gemm_plan(256, 128256, 4096, 0, 1)[0] == 10 and B.gllm_op_gemm_plan(289, 128256, 4096, 0, 1)[0] == 12
+    assert B.gllm_op_gemm_plan(2048, 4096, 14336, 0, 8) == (10, 2) and B.gllm_op_gemm_plan(2048, 4096, 4096, 0, 8) == (3, 2)
     with pytest.raises(B.GllmError):
         B.gllm_op_gemm_plan(128, 100, 4096, 0, 8)

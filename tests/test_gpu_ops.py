@@ -22,7 +22,7 @@ def padded_rows(bits, rows):
     return out
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6, 7])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6, 7, 10])
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (52, 512, 256), (300, 768, 192), (257, 1280, 704), (1024, 256, 2048)])
 def test_gemm_store_and_add(M, N, K, tile):
     print(f"gemm store/add M={M} N={N} K={K} tile={tile}", flush=True)
@@ -43,7 +43,7 @@ def test_gemm_store_and_add(M, N, K, tile):
     assert np.abs(got2 - 2 * ref).max() <= 4e-5 * scale + 1e-6
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6, 7])
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2, 3, 6, 7, 10])
 @pytest.mark.parametrize("M,I,K", [(52, 768, 256), (130, 128, 128), (300, 1408, 320)])
 def test_gemm_swiglu(M, I, K, tile):
     print(f"gemm swiglu M={M} I={I} K={K} tile={tile}", flush=True)
@@ -96,22 +96,23 @@ def test_gemm_256x192_tile(M, N, K):
     assert np.abs(got - 2 * ref).max() <= 4e-5 * np.abs(ref).max() + 1e-6
 
 
+@pytest.mark.parametrize("rowmix", [8, 12])
 @pytest.mark.parametrize("M", [257, 300, 320, 384, 600, 832])
-def test_gemm_row_mixed_launch(M):
+def test_gemm_row_mixed_launch(M, rowmix):
     """Whole bands of 256 rows as 256x256 tiles plus a last band of 64 (up to 64 rows left) or 128 rows: store, add,
-    SwiGLU and split-K planes."""
+    SwiGLU and split-K planes; tile 12 is the same with a third LDS stage for the weight tile."""
     N, K = 768, 384
-    print(f"gemm row-mixed launch M={M}", flush=True)
+    print(f"gemm row-mixed launch M={M} tile={rowmix}", flush=True)
     a = rand_bits(9, 1, (M, K), 1.0)
     w = rand_bits(9, 2, (N, K), 0.05)
     ref = oracle.linear(oracle.bf16_to_f64(a), w)
     Mp = (M + 255) // 256 * 256
     da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w)
     out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
-    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, 8)
-    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, 8)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, rowmix)
+    B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, rowmix)
     planes = torch.full((2, M, N), 9.0, dtype=torch.float32, device=DEV)
-    B.gllm_op_gemm_bf16_splitk(da, dw, planes, M, N, K, 8, 2)
+    B.gllm_op_gemm_bf16_splitk(da, dw, planes, M, N, K, rowmix, 2)
     torch.cuda.synchronize()
     scale = np.abs(ref).max()
     assert np.abs(out.cpu().numpy().astype(np.float64) - 2 * ref).max() <= 4e-5 * scale + 1e-6
@@ -126,7 +127,7 @@ def test_gemm_row_mixed_launch(M):
     x = oracle.bf16_to_f64(a)
     ref_s = oracle.swiglu(oracle.linear(x, wg), oracle.linear(x, wu))
     act = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
-    B.gllm_op_gemm_bf16(da, to_dev_bits(packed), act, M, 2 * I, K, B.GEMM_SWIGLU_BF16, 8)
+    B.gllm_op_gemm_bf16(da, to_dev_bits(packed), act, M, 2 * I, K, B.GEMM_SWIGLU_BF16, rowmix)
     torch.cuda.synchronize()
     err = np.abs(oracle.bf16_to_f64(bits_of(act)) - ref_s)
     assert np.all(err <= np.abs(ref_s) * 2.0 ** -7 + 1e-4), float(err.max())
@@ -166,7 +167,7 @@ def test_gemm_row_mixed_launch_refuses_shapes_without_a_short_last_band():
         assert e.value.status == -7          # GLLM_E_UNSUPPORTED
 
 
-@pytest.mark.parametrize("tile", [-1, 4])
+@pytest.mark.parametrize("tile", [-1, 4, 11])
 @pytest.mark.parametrize("mode", ["store", "swiglu"])
 def test_gemm_mixed_tile_launch(mode, tile):
     """A grid whose last round of 256x256 tiles would be partial: 320 tiles -> 256 big + 128 half-width tiles."""
@@ -199,7 +200,7 @@ def test_gemm_mixed_tile_launch(mode, tile):
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-4)
 
 
-@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2), (6, 2), (7, 4)])
+@pytest.mark.parametrize("tile,splits", [(0, 2), (3, 2), (3, 4), (2, 4), (-1, 2), (6, 2), (7, 4), (10, 2), (10, 8)])
 def test_gemm_split_k_planes_sum_to_the_product(tile, splits):
     M, N, K = 300, 512, 1024
     print(f"gemm split-K tile={tile} splits={splits}", flush=True)
@@ -217,3 +218,19 @@ def test_gemm_split_k_planes_sum_to_the_product(tile, splits):
     ks = K // splits
     part0 = oracle.linear(x[:, :ks], np.ascontiguousarray(w[:, :ks]))
     assert np.abs(got[0] - part0).max() <= 2e-5 * np.abs(part0).max() + 1e-6
+
+
+def test_gemm_third_weight_stage_changes_no_bit():
+    """Tiles 10 / 11 / 12 are tiles 3 / 4 / 8 with one more LDS stage for the weight tile: the same products in the same
+    order, so the results must be bit-identical -- also with few k-steps (fewer than stages) and with split-K."""
+    for M, N, K, pair, splits in ((700, 1024, 64, (3, 10), 1), (700, 1024, 128, (3, 10), 1), (520, 768, 1152, (3, 10), 3),
+                                  (300, 768, 640, (8, 12), 2), (500, 40960, 192, (4, 11), 1)):
+        a = to_dev_bits(padded_rows(rand_bits(11, 1, (M, K), 1.0), (M + 255) // 256 * 256))
+        w = to_dev_bits(rand_bits(11, 2, (N, K), 0.05))
+        outs = []
+        for tile in pair:
+            planes = torch.full((splits, M, N), 5.0, dtype=torch.float32, device=DEV)
+            B.gllm_op_gemm_bf16_splitk(a, w, planes, M, N, K, tile, splits)
+            outs.append(planes)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], outs[1]), (M, N, K, pair, splits)
