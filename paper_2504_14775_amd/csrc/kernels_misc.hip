@@ -65,6 +65,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t* __restrict__
         keep[i] = v;
         ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     }
+    // the gains are fetched before the reduction's barriers, so that their latency overlaps the row's (with a few
+    // hundred rows this kernel is a chain of latencies, not a stream)
+    f32x4 gain[MAXV];
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int j = (threadIdx.x + i * 256) * 4;
+        gain[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (j < hidden) gain[i] = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(gamma + j), f32x4);
+    }
     const float total = block_sum_256(ss, red);
     const float inv = 1.0f / sqrtf(total / (float)hidden + eps);
     bf16_t* hr = h + row * ldh;
@@ -72,10 +81,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t* __restrict__
     for (int i = 0; i < MAXV; ++i) {
         const int j = (threadIdx.x + i * 256) * 4;
         if (j < hidden) {
-            const f32x4 g = __builtin_convertvector(*reinterpret_cast<const bf16x4*>(gamma + j), f32x4);
             f32x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = keep[i][e] * inv * g[e];
+            for (int e = 0; e < 4; ++e) o[e] = keep[i][e] * inv * gain[i][e];
             *reinterpret_cast<bf16x4*>(hr + j) = __builtin_convertvector(o, bf16x4);
         }
     }
