@@ -455,3 +455,65 @@ def test_row_mixed_option_belongs_to_one_stage():
     assert torch.equal(out_a, ref_a)                                    # a's plan is unchanged
     assert torch.allclose(out_a, out_b, rtol=0, atol=5e-3)              # same result either way (tile shapes and split counts may differ)
     a.stage.destroy(); b.stage.destroy()
+
+
+def test_empty_batch_and_batches_at_the_stage_limits():
+    """Degenerate and extreme batches: no sequences at all (nothing is enqueued, nothing changes); one token on its own
+    (first token of a sequence: attends to itself only, so the attention output is its own V); a batch that uses every
+    row, every sequence and the last position the stage was created for; one more of any of them is refused."""
+    print("empty batch and limits", flush=True)
+    shape = synth.SHAPES["tiny"]
+    w = layer_weights_np(shape, 6)
+    limit = synth.build_batch([(40, 88), (1, 127), (23, 0)], 6, spare_blocks=2)      # 64 rows, 3 sequences, positions up to 128
+    cfg = B.make_config(shape, 64, 3, 8, 128)
+    st = B.Stage(cfg)
+    ws = torch.empty(st.workspace_bytes(), dtype=torch.uint8, device=DEV)
+    st.bind_workspace(ws)
+    for l, lw in enumerate(w):
+        st.load_layer(l, {k: to_dev_bits(v) for k, v in lw.items()})
+    kp0, vp0 = pool_np(shape, 6, limit.num_blocks)
+    dk, dv = to_dev_bits(kp0), to_dev_bits(vp0)
+    st.bind_kv_pool(dk, dv, limit.num_blocks)
+    x = hidden_np(shape, 6, 64)
+    out = torch.zeros(64, shape.hidden, dtype=torch.bfloat16, device=DEV)
+    # no sequences
+    st.forward(np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros((0, 8), np.int32), to_dev_bits(x), out)
+    torch.cuda.synchronize()
+    assert int(out.view(torch.int16).abs().sum()) == 0
+    assert np.array_equal(bits_of(dk), kp0) and np.array_equal(bits_of(dv), vp0)
+    # exactly at the limits: against the oracle
+    kp, vp = kp0.copy(), vp0.copy()
+    ref, _ = oracle.stage_forward(shape, w, limit.new_tokens, limit.cached_len, limit.block_tables, limit.num_blocks, kp, vp, x)
+    out32 = torch.empty(64, shape.hidden, dtype=torch.float32, device=DEV)
+    st.forward(limit.new_tokens, limit.cached_len, limit.block_tables, to_dev_bits(x), out, out32)
+    torch.cuda.synchronize()
+    r = dict(ref=ref, out=bits_of(out), out32=out32.cpu().numpy())
+    assert_output("limits", r, literal=True)
+    mk, mv = written_mask(shape, limit)
+    check_pool("K", bits_of(dk), kp0, kp, mask=mk)
+    check_pool("V", bits_of(dv), vp0, vp, mask=mv)
+    # one past each limit
+    def status_of(nt, cl, bt):
+        try:
+            st.forward(np.asarray(nt, np.int32), np.asarray(cl, np.int32), bt, to_dev_bits(x), out)
+        except B.GllmError as e:
+            return e.status
+        return 0
+    bt = limit.block_tables
+    assert status_of([41, 1, 23], limit.cached_len, bt) == -2                   # 65 rows
+    assert status_of([40, 1, 23], [88, 128, 0], bt) == -2                       # position 129
+    four = np.concatenate([bt, bt[:1]])
+    assert status_of([40, 1, 22, 1], [88, 127, 0, 0], four) == -1               # a fourth sequence
+    # a single first token: softmax over one key
+    one = synth.build_batch([(1, 0)], 7)
+    kp1, vp1 = pool_np(shape, 7, one.num_blocks)
+    d1k, d1v = to_dev_bits(kp1), to_dev_bits(vp1)
+    st.bind_kv_pool(d1k, d1v, one.num_blocks)
+    k1, v1 = kp1.copy(), vp1.copy()
+    ref1, _ = oracle.stage_forward(shape, w, one.new_tokens, one.cached_len, one.block_tables, one.num_blocks, k1, v1, x[:1])
+    o1 = torch.empty(1, shape.hidden, dtype=torch.bfloat16, device=DEV); o132 = torch.empty(1, shape.hidden, dtype=torch.float32, device=DEV)
+    bt1 = np.full((1, 8), -1, np.int32); bt1[0, 0] = one.block_tables[0, 0]
+    st.forward(one.new_tokens, one.cached_len, bt1, to_dev_bits(x[:1]), o1, o132)
+    torch.cuda.synchronize()
+    assert_output("one token", dict(ref=ref1, out=bits_of(o1), out32=o132.cpu().numpy()), literal=True)
+    st.destroy()
