@@ -238,15 +238,19 @@ def main():
     # ---- what this GPU sustains on a bare MFMA loop (bf16 operands like the GEMMs') and a bare streaming read ----
     sink = torch.randn(8192, device=dev).to(torch.bfloat16)
     probe = torch.empty(4 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     binding.gllm_op_peak_mfma(sink, 1024, 500); binding.gllm_op_peak_read(probe, probe.numel(), sink, 16384)
+    binding.gllm_op_peak_read(probe, probe.numel(), sink, 16384, non_temporal=True)
     ev[0].record(); binding.gllm_op_peak_mfma(sink, 1024, 4000); ev[1].record()
     ev[2].record(); binding.gllm_op_peak_read(probe, probe.numel(), sink, 16384); ev[3].record()
+    ev[4].record(); binding.gllm_op_peak_read(probe, probe.numel(), sink, 16384, non_temporal=True); ev[5].record()
     torch.cuda.synchronize()
     extra["ceiling_probes"] = {
         "mfma_loop_tflops": round(1024 * 4 * 4000 * 16 * 2 * 32 * 32 * 16 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12, 1),
         "stream_read_gbs": round(probe.numel() / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9, 1),
-        "note": "bare 32x32x16 bf16 MFMA loop on random operands / bare 16-byte streaming read of 4 GiB, same box"}
+        "stream_read_nontemporal_gbs": round(probe.numel() / (ev[4].elapsed_time(ev[5]) * 1e-3) / 1e9, 1),
+        "note": "bare 32x32x16 bf16 MFMA loop on random operands / bare 16-byte streaming read of 4 GiB, plain and with "
+                "the non-temporal hint, same box"}
     del probe
 
     # ---- CPU oracle on a bounded sample of the same batch ----

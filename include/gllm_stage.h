@@ -230,6 +230,8 @@ gllm_status gllm_op_rmsnorm(const float* x, const void* gamma_bf16, void* h_bf16
  * it (fill it with bf16 data of the kind the GEMMs see); it is never written in practice. */
 gllm_status gllm_op_peak_mfma(void* sink, int32_t workgroups, int32_t iters, void* stream);
 gllm_status gllm_op_peak_read(const void* src, int64_t bytes, void* sink, int32_t workgroups, void* stream);
+/* The same read with the non-temporal hint on every load (what the decode attention kernel uses for its K/V stream). */
+gllm_status gllm_op_peak_read_nt(const void* src, int64_t bytes, void* sink, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ EXPORTS = [
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
     "gllm_stage_bind_kv_pool", "gllm_stage_share_weights", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
-    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_gemm_plan", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read",
+    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_gemm_plan", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read", "gllm_op_peak_read_nt",
 ]
 
 
@@ -131,6 +131,8 @@ def load_library():
     lib.gllm_op_peak_mfma.argtypes = [vp, i32, i32, vp]
     lib.gllm_op_peak_read.restype = i32
     lib.gllm_op_peak_read.argtypes = [vp, i64, vp, i32, vp]
+    lib.gllm_op_peak_read_nt.restype = i32
+    lib.gllm_op_peak_read_nt.argtypes = [vp, i64, vp, i32, vp]
     _lib = lib
     return lib
 
@@ -283,8 +285,10 @@ def gllm_op_peak_mfma(sink, workgroups: int, iters: int, stream=None):
         raise GllmError(st, "gllm_op_peak_mfma")
 
 
-def gllm_op_peak_read(src, nbytes: int, sink, workgroups: int, stream=None):
-    st = load_library().gllm_op_peak_read(src.data_ptr(), nbytes, sink.data_ptr(), workgroups, _stream_ptr(stream))
+def gllm_op_peak_read(src, nbytes: int, sink, workgroups: int, stream=None, non_temporal: bool = False):
+    lib = load_library()
+    fn = lib.gllm_op_peak_read_nt if non_temporal else lib.gllm_op_peak_read
+    st = fn(src.data_ptr(), nbytes, sink.data_ptr(), workgroups, _stream_ptr(stream))
     if st != GLLM_OK:
         raise GllmError(st, "gllm_op_peak_read")
 

@@ -141,4 +141,4 @@ hipError_t launch_prefill_attention(const AttnArgs& a, const PrefillItem* items,
 // Ceiling probes (see kernels_peak.hip).  peak_mfma: workgroups x 4 waves x iters x 16 MFMAs of
 // 2*32*32*16 flop each.  peak_read: reads `bytes` once.
 hipError_t launch_peak_mfma(float* sink, int workgroups, int iters, hipStream_t stream);
-hipError_t launch_peak_read(const void* src, int64_t bytes, void* sink, int workgroups, hipStream_t stream);
+hipError_t launch_peak_read(const void* src, int64_t bytes, void* sink, int workgroups, hipStream_t stream, bool non_temporal = false);

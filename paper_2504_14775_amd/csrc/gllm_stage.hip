@@ -768,4 +768,9 @@ gllm_status gllm_op_peak_read(const void* src, int64_t bytes, void* sink, int32_
     return launch_peak_read(src, bytes, sink, workgroups, (hipStream_t)stream) == hipSuccess ? GLLM_OK : GLLM_E_HIP;
 }
 
+gllm_status gllm_op_peak_read_nt(const void* src, int64_t bytes, void* sink, int32_t workgroups, void* stream) {
+    if (!src || !sink || bytes < 16 || workgroups < 1) return GLLM_E_INVALID;
+    return launch_peak_read(src, bytes, sink, workgroups, (hipStream_t)stream, true) == hipSuccess ? GLLM_OK : GLLM_E_HIP;
+}
+
 }  // extern "C"

@@ -34,6 +34,9 @@ struct KvFrag {
     u32x4 v[D / 16];     // [16-dim block]: slots 8 (G & 1) .. + 7 of dim r of page G >> 1
 };
 
+// The loads carry the non-temporal hint: a decode row's K and V are read once and never again, and without the hint the
+// stream is allocated in the caches on its way (measured: 5.78 -> 6.20 TB/s on 256 rows of 512 .. 4096 keys, 5.94 -> 6.35
+// on 512 rows of 1024 .. 8192 keys; a bare streaming read without the hint sustains 5.9 - 6.2).
 template <int D>
 __device__ __forceinline__ void load_kv(KvFrag<D>& f, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
                                         int64_t page0, int64_t page1, int n_kv, int kvh, int lane) {
@@ -45,9 +48,9 @@ __device__ __forceinline__ void load_kv(KvFrag<D>& f, const bf16_t* __restrict__
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int s = 0; s < D / 32; ++s) f.k[t][s] = *reinterpret_cast<const u32x4*>(kb + s * 512 + t * 32);
+        for (int s = 0; s < D / 32; ++s) f.k[t][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + s * 512 + t * 32));
 #pragma unroll
-    for (int b = 0; b < D / 16; ++b) f.v[b] = *reinterpret_cast<const u32x4*>(vb + b * 256);
+    for (int b = 0; b < D / 16; ++b) f.v[b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + b * 256));
 }
 
 // State of NB column groups across the key loop.

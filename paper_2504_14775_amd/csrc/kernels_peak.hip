@@ -29,18 +29,20 @@ __global__ __launch_bounds__(256) void peak_mfma_kernel(float* __restrict__ sink
     if (s == 12345.678f) sink[0] = s;  // keeps the loop alive
 }
 
-// Grid-stride read of `count16` 16-byte words; one partial sum per thread is kept live.
+// Grid-stride read of `count16` 16-byte words; one partial sum per thread is kept live.  NT: with the non-temporal hint.
+template <bool NT>
 __global__ __launch_bounds__(256) void peak_read_kernel(const u32x4* __restrict__ src, int64_t count16,
                                                          uint32_t* __restrict__ sink) {
     const int64_t stride = (int64_t)gridDim.x * 256;
     uint32_t s = 0;
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    auto ld = [&](int64_t j) { return NT ? __builtin_nontemporal_load(src + j) : src[j]; };
     for (; i + 3 * stride < count16; i += 4 * stride) {
-        u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        u32x4 a = ld(i), b = ld(i + stride), c = ld(i + 2 * stride), d = ld(i + 3 * stride);
         s += a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3] ^ c[0] ^ c[1] ^ c[2] ^ c[3] ^ d[0] ^ d[1] ^ d[2] ^ d[3];
     }
     for (; i < count16; i += stride) {
-        u32x4 a = src[i];
+        u32x4 a = ld(i);
         s += a[0] ^ a[1] ^ a[2] ^ a[3];
     }
     if (s == 0x9E3779B9u) sink[0] = s;
@@ -53,7 +55,8 @@ hipError_t launch_peak_mfma(float* sink, int workgroups, int iters, hipStream_t 
     return hipGetLastError();
 }
 
-hipError_t launch_peak_read(const void* src, int64_t bytes, void* sink, int workgroups, hipStream_t stream) {
-    peak_read_kernel<<<workgroups, 256, 0, stream>>>((const u32x4*)src, bytes / 16, (uint32_t*)sink);
+hipError_t launch_peak_read(const void* src, int64_t bytes, void* sink, int workgroups, hipStream_t stream, bool non_temporal) {
+    if (non_temporal) peak_read_kernel<true><<<workgroups, 256, 0, stream>>>((const u32x4*)src, bytes / 16, (uint32_t*)sink);
+    else peak_read_kernel<false><<<workgroups, 256, 0, stream>>>((const u32x4*)src, bytes / 16, (uint32_t*)sink);
     return hipGetLastError();
 }
