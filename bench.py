@@ -98,6 +98,8 @@ def main():
     import numpy as np
     import torch
     from paper_2504_14775_amd import binding, synth
+    if os.environ.get("GLLM_STAGE_LIBRARY"):      # another build of the library (experiments)
+        binding.LIB_PATH = os.path.abspath(os.environ["GLLM_STAGE_LIBRARY"])
 
     if not torch.cuda.is_available():
         sys.stderr.write("bench.py: no GPU visible; the stage has no CPU path.\n")
