@@ -44,6 +44,7 @@ def main():
         tile, splits = B.gllm_op_gemm_plan(T, n, k, mode, ms)
         copies = max(2, int(600e6 // (n * k * 2)) + 1)
         a = torch.randn(Tp, k, device=dev).to(torch.bfloat16)
+        # random values: the buffers are read as the tiled weight layout, which for a random matrix is a random matrix
         ws = [(torch.randn(n, k, device=dev) * 0.02).to(torch.bfloat16) for _ in range(copies)]
         if mode == B.GEMM_SWIGLU_BF16:
             out = torch.zeros(T, n // 2, device=dev, dtype=torch.bfloat16)

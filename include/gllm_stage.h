@@ -186,7 +186,18 @@ const char* gllm_profile_class_name(int32_t i);
 /* ---- single operations on DEVICE buffers (the kernels the stage is built from), exported so
  * that each can be tested and timed on its own.  All enqueue on `stream` and return. ---- */
 
-/* out[m][n] (op)= sum_k a[m][k] * w[n][k];  a: bf16 [m_rows][lda] with lda >= k, w: bf16 [n][ldw].
+/* The weight operand of the GEMMs below is "tiled": blocks of 64 output rows x 64 k values, each block contiguous
+ * (64 rows of 128 bytes), blocks ordered [row block][k block]; element (r, c) of an [n][k] matrix sits at element index
+ *   ((r/64)*(k/64) + c/64)*4096 + (r%64)*64 + c%64.
+ * (A k-step of a workgroup tile then reads whole 8 KiB pieces, not one 128-byte piece per output row: with few token
+ * rows the weights stream from HBM once per call, and HBM serves long pieces better.)  gllm_op_pack_weight writes this
+ * layout from a row-major bf16 matrix w [n][ldw] (DEVICE, 16-byte aligned, ldw >= k and a multiple of 8) into
+ * out (DEVICE, n*k elements, must not overlap w); n and k multiples of 64, else GLLM_E_UNSUPPORTED.  The stage and the
+ * head repack the row-major weights they are given in the same way when these are loaded. */
+gllm_status gllm_op_pack_weight(const void* w, int64_t ldw, int32_t n, int32_t k, void* out, void* stream);
+
+/* out[m][n] (op)= sum_k a[m][k] * w[n][k];  a: bf16 [m_rows][lda] with lda >= k, w: bf16, n rows, tiled as above with
+ * k extent ldw (a multiple of 64, >= k: the product may use a leading part of the k range).
  * Requirements: k a multiple of 64 and n a multiple of 128 (the stage pads its operands);
  * a must be readable for round_up(m,256) rows.  mode: 0 store fp32 to out[m][ldc];
  * 1 add into fp32 out[m][ldc]; 2 SwiGLU: columns come in groups of 64 = 32 gate + 32 up

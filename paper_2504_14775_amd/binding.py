@@ -25,7 +25,7 @@ EXPORTS = [
     "gllm_stage_workspace_bytes", "gllm_stage_bind_workspace", "gllm_stage_load_layer",
     "gllm_stage_bind_kv_pool", "gllm_stage_share_weights", "gllm_stage_set_alias_check", "gllm_stage_set_option", "gllm_stage_forward",
     "gllm_stage_set_profiling", "gllm_stage_read_profile", "gllm_profile_num_classes",
-    "gllm_profile_class_name", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_gemm_plan", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read", "gllm_op_peak_read_nt",
+    "gllm_profile_class_name", "gllm_op_pack_weight", "gllm_op_gemm_bf16", "gllm_op_gemm_bf16_splitk", "gllm_op_gemm_plan", "gllm_op_rmsnorm", "gllm_op_peak_mfma", "gllm_op_peak_read", "gllm_op_peak_read_nt",
 ]
 
 
@@ -119,6 +119,8 @@ def load_library():
     lib.gllm_profile_num_classes.argtypes = []
     lib.gllm_profile_class_name.restype = C.c_char_p
     lib.gllm_profile_class_name.argtypes = [i32]
+    lib.gllm_op_pack_weight.restype = i32
+    lib.gllm_op_pack_weight.argtypes = [vp, i64, i32, i32, vp, vp]
     lib.gllm_op_gemm_bf16.restype = i32
     lib.gllm_op_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
     lib.gllm_op_gemm_bf16_splitk.restype = i32
@@ -242,8 +244,17 @@ class Stage:
         return {self.lib.gllm_profile_class_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
+def gllm_op_pack_weight(w, out, stream=None):
+    """w: bf16 [n, k] row-major (device); out: bf16, n*k elements, receives the GEMM's tiled weight layout."""
+    lib = load_library()
+    st = lib.gllm_op_pack_weight(w.data_ptr(), w.stride(0), w.shape[0], w.shape[1], out.data_ptr(), _stream_ptr(stream))
+    if st != GLLM_OK:
+        raise GllmError(st, "gllm_op_pack_weight")
+
+
 def gllm_op_gemm_bf16(a, w, out, m: int, n: int, k: int, mode: int, tile: int = -1, lda=None, ldw=None, ldc=None,
                       stream=None):
+    """w: a [n, k] tensor holding the tiled layout gllm_op_pack_weight writes (its row stride is taken as the k extent)."""
     lib = load_library()
     st = lib.gllm_op_gemm_bf16(a.data_ptr(), lda or a.stride(0), w.data_ptr(), ldw or w.stride(0), out.data_ptr(),
                                ldc or out.stride(0), m, n, k, mode, tile, _stream_ptr(stream))

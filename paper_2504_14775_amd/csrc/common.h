@@ -24,6 +24,16 @@ constexpr int kGemmPadN = 256;   // packed weight rows are padded to a multiple 
 constexpr int kGemmPadK = 64;    // packed weight columns / activation row strides are multiples of this
 constexpr int kSwigluGroup = 32; // gate/up interleave granularity of the packed gate-up matrix
 
+// Weight operand of every GEMM here ("tiled"): blocks of 64 output rows x 64 k values, a block contiguous (64 rows of
+// 128 bytes = 8 KiB), blocks ordered [row block][k block].  A k-step of a workgroup tile then reads whole 8 KiB pieces
+// instead of one 128-byte piece per output row, which is what HBM serves well when the weights stream (few token rows).
+// Element (n, k) of an [N][K] matrix, N and K multiples of 64:
+constexpr int kWBlock = 64;
+constexpr int kWBlockBytes = kWBlock * kWBlock * 2;
+__host__ __device__ static inline int64_t w_tiled_index(int64_t n, int64_t k, int64_t K) {
+    return (((n >> 6) * (K >> 6) + (k >> 6)) << 12) + ((n & 63) << 6) + (k & 63);
+}
+
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -31,7 +41,8 @@ enum GemmMode { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 
 // ---- launchers (each enqueues on `stream` and returns the launch status) ----------------
 
-// out (op)= a[m x k] * w[n x k]^T, see gllm_op_gemm_bf16 in the public header.
+// out (op)= a[m x k] * w[n x k]^T, see gllm_op_gemm_bf16 in the public header; w is tiled (w_tiled_index) with ldw its k
+// extent (a multiple of 64, >= k).
 // tile: -1 picks a tile shape from m and n; 0..3 force one (128x128, 256x128, 256x256, 256x256 with 8 waves);
 // 4 forces the mixed 256x256 + 256x128 launch (only where gemm_mixed_rem_cols(m, n) > 0); 5 = 256x192 (not SwiGLU);
 // 6 = 128x128 with four LDS stages; 7 = 64x128 with three LDS stages (up to 64 rows per tile row: weight streaming);
@@ -60,11 +71,14 @@ hipError_t launch_add_rmsnorm(float* x, const float* y, int planes, int64_t plan
 hipError_t launch_add_cast_out(const float* x, const float* y, int planes, int64_t plane_stride, bf16_t* out,
                                float* out_f32, int64_t count, hipStream_t stream);
 
-// Weight repacking (device to device).
-hipError_t launch_copy_rows_padded(const bf16_t* src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_row0,
-                                   hipStream_t stream);
+// Weight repacking (device to device) into the tiled layout: rows [dst_row0, dst_row0 + rows) x columns [0, cols) of a
+// tiled matrix whose k extent is k_dst come from the row-major src (row stride ld_src); cols a multiple of 8.  What lies
+// outside stays as it is (the caller zeroes the padding).
+hipError_t launch_pack_rows_tiled(const bf16_t* src, int64_t ld_src, int rows, int cols, bf16_t* dst, int64_t k_dst,
+                                  int dst_row0, hipStream_t stream);
+// The gate/up matrix, rows interleaved in groups of kSwigluGroup (gate group, then the matching up group), tiled.
 hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, int hidden, bf16_t* dst,
-                               int64_t ld_dst, hipStream_t stream);
+                               int64_t k_dst, hipStream_t stream);
 
 // A run of consecutive new tokens of one sequence that fall into one page: rows row0 .. row0 + n - 1 go to slots
 // slot0 .. slot0 + n - 1 of `page`.

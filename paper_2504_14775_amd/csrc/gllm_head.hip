@@ -53,17 +53,13 @@ __global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const float* __rest
     }
 }
 
-// rows of w [vocab][hidden] -> padded [vocab_pad][hidden], zero rows past vocab
+// rows of w [vocab][hidden] -> the GEMM's tiled weight layout with vocab_pad rows, zero rows past vocab
 __global__ __launch_bounds__(256) void pad_rows_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ out, int vocab,
                                                        int hidden) {
     const int v = blockIdx.x;
     const u32x4* src = reinterpret_cast<const u32x4*>(w + (int64_t)v * hidden);
-    u32x4* dst = reinterpret_cast<u32x4*>(out + (int64_t)v * hidden);
-    if (v < vocab) {
-        for (int i = threadIdx.x; i < hidden / 8; i += 256) dst[i] = src[i];
-    } else {
-        for (int i = threadIdx.x; i < hidden / 8; i += 256) dst[i] = u32x4{0u, 0u, 0u, 0u};
-    }
+    for (int i = threadIdx.x; i < hidden / 8; i += 256)
+        *reinterpret_cast<u32x4*>(out + w_tiled_index(v, i * 8, hidden)) = v < vocab ? src[i] : u32x4{0u, 0u, 0u, 0u};
 }
 
 // ---- sampling: one workgroup per row ----------------------------------------------------------------------

@@ -358,12 +358,12 @@ gllm_status gllm_stage_load_layer(gllm_stage* s, int32_t layer, const gllm_layer
     LayerBuffers& L = s->layers[layer];
     const int H = c.hidden;
     if (!L.wqkv) HIP_TRY(s, alloc_layer(s, L, st));
-    HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wq, s->q_dim, H, L.wqkv, H, 0, st));
-    HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wk, s->kv_dim, H, L.wqkv, H, s->q_dim, st));
-    HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wv, s->kv_dim, H, L.wqkv, H, s->q_dim + s->kv_dim, st));
-    HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wo, H, s->q_dim, L.wo, s->q_dim, 0, st));
+    HIP_TRY(s, launch_pack_rows_tiled((const bf16_t*)w->wq, H, s->q_dim, H, L.wqkv, H, 0, st));
+    HIP_TRY(s, launch_pack_rows_tiled((const bf16_t*)w->wk, H, s->kv_dim, H, L.wqkv, H, s->q_dim, st));
+    HIP_TRY(s, launch_pack_rows_tiled((const bf16_t*)w->wv, H, s->kv_dim, H, L.wqkv, H, s->q_dim + s->kv_dim, st));
+    HIP_TRY(s, launch_pack_rows_tiled((const bf16_t*)w->wo, s->q_dim, H, s->q_dim, L.wo, s->q_dim, 0, st));
     HIP_TRY(s, launch_pack_gate_up((const bf16_t*)w->wgate, (const bf16_t*)w->wup, c.intermediate, H, L.wgu, H, st));
-    HIP_TRY(s, launch_copy_rows_padded((const bf16_t*)w->wdown, H, c.intermediate, L.wd, s->inter_pad, 0, st));
+    HIP_TRY(s, launch_pack_rows_tiled((const bf16_t*)w->wdown, c.intermediate, H, c.intermediate, L.wd, s->inter_pad, 0, st));
     HIP_TRY(s, hipMemcpyAsync(L.norm1, w->norm1, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     HIP_TRY(s, hipMemcpyAsync(L.norm2, w->norm2, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     if (c.has_qkv_bias) {
@@ -738,6 +738,14 @@ gllm_status gllm_op_gemm_bf16_splitk(const void* a, int64_t lda, const void* w, 
     hipError_t e = launch_gemm_bf16((const bf16_t*)a, lda, (const bf16_t*)w, ldw, out, ldc, m, n, k, GEMM_STORE_F32, tile,
                                     splits, plane_stride, (hipStream_t)stream);
     return e == hipSuccess ? GLLM_OK : (e == hipErrorInvalidValue ? GLLM_E_UNSUPPORTED : GLLM_E_HIP);
+}
+
+gllm_status gllm_op_pack_weight(const void* w, int64_t ldw, int32_t n, int32_t k, void* out, void* stream) {
+    if (!w || !out || n < 1 || k < 1) return GLLM_E_INVALID;
+    if (n % kWBlock != 0 || k % kWBlock != 0 || ldw < k || ldw % 8 != 0 || ((uintptr_t)w & 15) || ((uintptr_t)out & 15))
+        return GLLM_E_UNSUPPORTED;
+    hipError_t e = launch_pack_rows_tiled((const bf16_t*)w, ldw, n, k, (bf16_t*)out, k, 0, (hipStream_t)stream);
+    return e == hipSuccess ? GLLM_OK : GLLM_E_HIP;
 }
 
 gllm_status gllm_op_gemm_plan(int32_t m, int32_t n, int32_t k, int32_t mode, int32_t max_splits, int32_t* tile,

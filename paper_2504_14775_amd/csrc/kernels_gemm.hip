@@ -94,9 +94,12 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     const int lq = (lane & 15) ^ ((4 * (wave & 1) + lline) & 7);
     const int lrow = 2 * lline + (lq >> 3), lgrp = lq & 7;
     const uint32_t voff_a = (uint32_t)(lrow * lda + lgrp * 8) * 2u;
-    const uint32_t voff_w = (uint32_t)(lrow * ldw + lgrp * 8) * 2u;
+    // W is tiled (see w_tiled_index): a group's 8 rows x 64 k values are 1 KiB in a row, a 64-row block 8 KiB, so a load
+    // instruction reads one contiguous KiB and a k-step of the tile whole 8 KiB pieces
+    const uint32_t voff_w = (uint32_t)(lrow * 64 + lgrp * 8) * 2u;
+    const int64_t w_blocks_k = ldw >> 6;
     const char* a_tile = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
-    const char* w_tile = reinterpret_cast<const char*>(W + (int64_t)n0 * ldw);
+    const char* w_tile = reinterpret_cast<const char*>(W) + (int64_t)(n0 >> 6) * w_blocks_k * kWBlockBytes;
     // tile kt of A into A stage `stage` / of W into W stage `stage` (wave w fills groups w, w + NW, ...)
     auto issue_a = [&](int kt, int stage) {
         unsigned char* sbase = smem + stage * A_STAGE;
@@ -109,11 +112,11 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     };
     auto issue_w = [&](int kt, int stage) {
         unsigned char* sbase = smem + W_BASE + stage * W_STAGE;
-        const int64_t kbyte = (int64_t)(kt + kt_base) * (BK * 2);
+        const char* w_kt = w_tile + (int64_t)(kt + kt_base) * kWBlockBytes + voff_w;
 #pragma unroll
         for (int i = 0; i < GW; ++i) {
-            const int g = wave + i * NW;
-            __builtin_amdgcn_global_load_lds((gptr_t)(w_tile + (int64_t)(g * 8) * ldw * 2 + kbyte + voff_w), (lptr_t)(sbase + g * 1024), 16, 0, 0);
+            const int g = wave + i * NW;  // rows 8g .. 8g+7 of the tile: row block g / 8, KiB g % 8 of that block
+            __builtin_amdgcn_global_load_lds((gptr_t)(w_kt + (int64_t)(g >> 3) * w_blocks_k * kWBlockBytes + (g & 7) * 1024), (lptr_t)(sbase + g * 1024), 16, 0, 0);
         }
     };
 
@@ -536,7 +539,7 @@ hipError_t launch_gemm_bf16(const bf16_t* a, int64_t lda, const bf16_t* w, int64
                             hipStream_t stream) {
     if (m <= 0) return hipSuccess;
     if (n <= 0 || k <= 0 || n % 64 != 0 || k % BK != 0) return hipErrorInvalidValue;
-    if (lda * 16 >= (int64_t)1 << 31 || ldw * 16 >= (int64_t)1 << 31) return hipErrorInvalidValue;
+    if (lda * 16 >= (int64_t)1 << 31 || ldw % kWBlock != 0 || ldw < k) return hipErrorInvalidValue;
     if (splits < 1 || (k / BK) % splits != 0) return hipErrorInvalidValue;
     if (splits > 1 && mode != GEMM_STORE_F32) return hipErrorInvalidValue;
     if (tile < 0) {

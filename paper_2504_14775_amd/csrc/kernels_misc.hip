@@ -100,30 +100,32 @@ __global__ __launch_bounds__(256) void cast_out_kernel(const float* __restrict__
     if (out_f32) reinterpret_cast<f32x4*>(out_f32)[i] = v;
 }
 
-// dst[(dst_row0 + r)][c] = src[r][c] for c < cols; the padding is left as it is (zeroed by the caller).
-__global__ __launch_bounds__(256) void copy_rows_kernel(const bf16_t* __restrict__ src, int rows, int cols,
-                                                         bf16_t* __restrict__ dst, int64_t ld_dst, int dst_row0) {
+// Element (dst_row0 + r, c) of the tiled dst (k extent k_dst) = src[r][c] for c < cols; the padding is left as it is
+// (zeroed by the caller).
+__global__ __launch_bounds__(256) void pack_rows_tiled_kernel(const bf16_t* __restrict__ src, int64_t ld_src, int rows,
+                                                               int cols, bf16_t* __restrict__ dst, int64_t k_dst,
+                                                               int dst_row0) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one 8-element group per thread
     int groups = cols / 8;
     if (i >= (int64_t)rows * groups) return;
     int r = (int)(i / groups), g = (int)(i % groups);
-    *reinterpret_cast<u32x4*>(dst + (int64_t)(dst_row0 + r) * ld_dst + g * 8) =
-        *reinterpret_cast<const u32x4*>(src + (int64_t)r * cols + g * 8);
+    *reinterpret_cast<u32x4*>(dst + w_tiled_index(dst_row0 + r, g * 8, k_dst)) =
+        *reinterpret_cast<const u32x4*>(src + (int64_t)r * ld_src + g * 8);
 }
 
 // Packed gate/up matrix: outputs are taken 32 at a time; packed rows 64b .. 64b+31 are the gate
 // rows 32b .. 32b+31, packed rows 64b+32 .. 64b+63 the matching up rows.
 __global__ __launch_bounds__(256) void pack_gate_up_kernel(const bf16_t* __restrict__ gate, const bf16_t* __restrict__ up,
                                                             int inter, int hidden, bf16_t* __restrict__ dst,
-                                                            int64_t ld_dst) {
+                                                            int64_t k_dst) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     int groups = hidden / 8;
     if (i >= (int64_t)inter * groups) return;
     int r = (int)(i / groups), g = (int)(i % groups);
     int64_t prow = (int64_t)(r / kSwigluGroup) * (2 * kSwigluGroup) + r % kSwigluGroup;
-    *reinterpret_cast<u32x4*>(dst + prow * ld_dst + g * 8) =
+    *reinterpret_cast<u32x4*>(dst + w_tiled_index(prow, g * 8, k_dst)) =
         *reinterpret_cast<const u32x4*>(gate + (int64_t)r * hidden + g * 8);
-    *reinterpret_cast<u32x4*>(dst + (prow + kSwigluGroup) * ld_dst + g * 8) =
+    *reinterpret_cast<u32x4*>(dst + w_tiled_index(prow + kSwigluGroup, g * 8, k_dst)) =
         *reinterpret_cast<const u32x4*>(up + (int64_t)r * hidden + g * 8);
 }
 
@@ -367,19 +369,21 @@ hipError_t launch_add_cast_out(const float* x, const float* y, int planes, int64
     return hipGetLastError();
 }
 
-hipError_t launch_copy_rows_padded(const bf16_t* src, int rows, int cols, bf16_t* dst, int64_t ld_dst, int dst_row0,
-                                   hipStream_t stream) {
+hipError_t launch_pack_rows_tiled(const bf16_t* src, int64_t ld_src, int rows, int cols, bf16_t* dst, int64_t k_dst,
+                                  int dst_row0, hipStream_t stream) {
+    if (cols % 8 || k_dst % kWBlock || cols > k_dst || ld_src < cols || dst_row0 < 0) return hipErrorInvalidValue;
     int64_t n = (int64_t)rows * (cols / 8);
     if (n <= 0) return hipSuccess;
-    copy_rows_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(src, rows, cols, dst, ld_dst, dst_row0);
+    pack_rows_tiled_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(src, ld_src, rows, cols, dst, k_dst, dst_row0);
     return hipGetLastError();
 }
 
 hipError_t launch_pack_gate_up(const bf16_t* gate, const bf16_t* up, int inter, int hidden, bf16_t* dst,
-                               int64_t ld_dst, hipStream_t stream) {
+                               int64_t k_dst, hipStream_t stream) {
+    if (hidden % 8 || k_dst % kWBlock || hidden > k_dst) return hipErrorInvalidValue;
     int64_t n = (int64_t)inter * (hidden / 8);
     if (n <= 0) return hipSuccess;
-    pack_gate_up_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(gate, up, inter, hidden, dst, ld_dst);
+    pack_gate_up_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, stream>>>(gate, up, inter, hidden, dst, k_dst);
     return hipGetLastError();
 }
 

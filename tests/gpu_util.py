@@ -15,6 +15,19 @@ def to_dev_bits(bits: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
 
 
+def tiled_bits(bits: np.ndarray) -> np.ndarray:
+    """A row-major [n][k] matrix in the weight layout the GEMM operations take (stated in include/gllm_stage.h): blocks
+    of 64 rows x 64 columns, each contiguous and row-major inside, ordered [row block][column block].  Returned with
+    the shape [n][k] the operations expect of the buffer."""
+    n, k = bits.shape
+    assert n % 64 == 0 and k % 64 == 0
+    return np.ascontiguousarray(bits.reshape(n // 64, 64, k // 64, 64).transpose(0, 2, 1, 3)).reshape(n, k)
+
+
+def to_dev_weight(bits: np.ndarray) -> torch.Tensor:
+    return to_dev_bits(tiled_bits(bits))
+
+
 def bits_of(t: torch.Tensor) -> np.ndarray:
     return synth.bf16_bits(t)
 

@@ -6,7 +6,7 @@ import torch
 import oracle
 from paper_2504_14775_amd import binding as B
 from paper_2504_14775_amd import synth
-from gpu_util import DEV, bits_of, to_dev_bits
+from gpu_util import DEV, bits_of, tiled_bits, to_dev_bits, to_dev_weight
 
 pytestmark = pytest.mark.gpu
 
@@ -30,7 +30,7 @@ def test_gemm_store_and_add(M, N, K, tile):
     w = rand_bits(1, 2, (N, K), 0.05)
     ref = oracle.linear(oracle.bf16_to_f64(a), w)
     Mp = (M + 255) // 256 * 256
-    da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w)
+    da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_weight(w)
     out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
     B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, tile)
     torch.cuda.synchronize()
@@ -60,7 +60,7 @@ def test_gemm_swiglu(M, I, K, tile):
         packed[64 * blk + 32: 64 * blk + 64] = wu[32 * blk: 32 * blk + 32]
     Mp = (M + 255) // 256 * 256
     out = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
-    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(packed), out, M, 2 * I, K, B.GEMM_SWIGLU_BF16, tile)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_weight(packed), out, M, 2 * I, K, B.GEMM_SWIGLU_BF16, tile)
     torch.cuda.synchronize()
     got = oracle.bf16_to_f64(bits_of(out))
     err = np.abs(got - ref)
@@ -89,8 +89,8 @@ def test_gemm_256x192_tile(M, N, K):
     Mp = (M + 255) // 256 * 256
     out = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV)
     wpad = np.zeros(((N + 255) // 256 * 256, K), dtype=np.uint16); wpad[:N] = w
-    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(wpad), out, M, N, K, B.GEMM_STORE_F32, 5)
-    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(wpad), out, M, N, K, B.GEMM_ADD_F32, 5)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_weight(wpad), out, M, N, K, B.GEMM_STORE_F32, 5)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_weight(wpad), out, M, N, K, B.GEMM_ADD_F32, 5)
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)
     assert np.abs(got - 2 * ref).max() <= 4e-5 * np.abs(ref).max() + 1e-6
@@ -107,7 +107,7 @@ def test_gemm_row_mixed_launch(M, rowmix):
     w = rand_bits(9, 2, (N, K), 0.05)
     ref = oracle.linear(oracle.bf16_to_f64(a), w)
     Mp = (M + 255) // 256 * 256
-    da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w)
+    da, dw = to_dev_bits(padded_rows(a, Mp)), to_dev_weight(w)
     out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
     B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, rowmix)
     B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, rowmix)
@@ -127,7 +127,7 @@ def test_gemm_row_mixed_launch(M, rowmix):
     x = oracle.bf16_to_f64(a)
     ref_s = oracle.swiglu(oracle.linear(x, wg), oracle.linear(x, wu))
     act = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
-    B.gllm_op_gemm_bf16(da, to_dev_bits(packed), act, M, 2 * I, K, B.GEMM_SWIGLU_BF16, rowmix)
+    B.gllm_op_gemm_bf16(da, to_dev_weight(packed), act, M, 2 * I, K, B.GEMM_SWIGLU_BF16, rowmix)
     torch.cuda.synchronize()
     err = np.abs(oracle.bf16_to_f64(bits_of(act)) - ref_s)
     assert np.all(err <= np.abs(ref_s) * 2.0 ** -7 + 1e-4), float(err.max())
@@ -142,7 +142,7 @@ def test_gemm_288_row_tile(M):
     a = rand_bits(10, 1, (M, K), 1.0)
     w = rand_bits(10, 2, (N, K), 0.05)
     ref = oracle.linear(oracle.bf16_to_f64(a), w)
-    da, dw = to_dev_bits(padded_rows(a, 512)), to_dev_bits(w)
+    da, dw = to_dev_bits(padded_rows(a, 512)), to_dev_weight(w)
     out = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
     B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_STORE_F32, 9)
     B.gllm_op_gemm_bf16(da, dw, out, M, N, K, B.GEMM_ADD_F32, 9)
@@ -154,7 +154,7 @@ def test_gemm_288_row_tile(M):
     assert np.abs(planes.cpu().numpy().astype(np.float64).sum(axis=0) - ref).max() <= 2e-5 * scale + 1e-6
     for m, n, mode in ((256, N, B.GEMM_STORE_F32), (289, N, B.GEMM_STORE_F32), (M, 512, B.GEMM_STORE_F32), (M, 768, B.GEMM_SWIGLU_BF16)):
         with pytest.raises(B.GllmError) as e:
-            B.gllm_op_gemm_bf16(da, to_dev_bits(rand_bits(10, 3, (768, K), 0.05)), torch.empty(512, 768, device=DEV), m, n, K, mode, 9)
+            B.gllm_op_gemm_bf16(da, to_dev_weight(rand_bits(10, 3, (768, K), 0.05)), torch.empty(512, 768, device=DEV), m, n, K, mode, 9)
         assert e.value.status == -7          # GLLM_E_UNSUPPORTED
 
 
@@ -180,7 +180,7 @@ def test_gemm_mixed_tile_launch(mode, tile):
         w = rand_bits(5, 2, (N, K), 0.05)
         ref = oracle.linear(x, w)
         out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
-        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w), out, M, N, K, B.GEMM_STORE_F32, tile)
+        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_weight(w), out, M, N, K, B.GEMM_STORE_F32, tile)
         torch.cuda.synchronize()
         got = out.cpu().numpy().astype(np.float64)
         assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-6
@@ -194,7 +194,7 @@ def test_gemm_mixed_tile_launch(mode, tile):
         pk[:, 0] = wg.reshape(I // 32, 32, K)
         pk[:, 1] = wu.reshape(I // 32, 32, K)
         out = torch.zeros((M, I), dtype=torch.bfloat16, device=DEV)
-        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(packed), out, M, N, K, B.GEMM_SWIGLU_BF16, tile)
+        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, Mp)), to_dev_weight(packed), out, M, N, K, B.GEMM_SWIGLU_BF16, tile)
         torch.cuda.synchronize()
         got = oracle.bf16_to_f64(bits_of(out))
         assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-4)
@@ -209,7 +209,7 @@ def test_gemm_split_k_planes_sum_to_the_product(tile, splits):
     ref = oracle.linear(oracle.bf16_to_f64(a), w)
     Mp = (M + 255) // 256 * 256
     planes = torch.full((splits, M, N), 9.0, dtype=torch.float32, device=DEV)
-    B.gllm_op_gemm_bf16_splitk(to_dev_bits(padded_rows(a, Mp)), to_dev_bits(w), planes, M, N, K, tile, splits)
+    B.gllm_op_gemm_bf16_splitk(to_dev_bits(padded_rows(a, Mp)), to_dev_weight(w), planes, M, N, K, tile, splits)
     torch.cuda.synchronize()
     got = planes.cpu().numpy().astype(np.float64)
     assert np.abs(got.sum(axis=0) - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-6
@@ -226,7 +226,7 @@ def test_gemm_third_weight_stage_changes_no_bit():
     for M, N, K, pair, splits in ((700, 1024, 64, (3, 10), 1), (700, 1024, 128, (3, 10), 1), (520, 768, 1152, (3, 10), 3),
                                   (300, 768, 640, (8, 12), 2), (500, 40960, 192, (4, 11), 1)):
         a = to_dev_bits(padded_rows(rand_bits(11, 1, (M, K), 1.0), (M + 255) // 256 * 256))
-        w = to_dev_bits(rand_bits(11, 2, (N, K), 0.05))
+        w = to_dev_weight(rand_bits(11, 2, (N, K), 0.05))
         outs = []
         for tile in pair:
             planes = torch.full((splits, M, N), 5.0, dtype=torch.float32, device=DEV)
@@ -234,3 +234,31 @@ def test_gemm_third_weight_stage_changes_no_bit():
             outs.append(planes)
         torch.cuda.synchronize()
         assert torch.equal(outs[0], outs[1]), (M, N, K, pair, splits)
+
+
+def test_pack_weight_writes_the_documented_tiled_layout():
+    """gllm_op_pack_weight against the layout as the header states it (gpu_util.tiled_bits), bit for bit: a whole matrix,
+    and a part of a wider one (row stride above k); then the product on a leading part of the packed k range."""
+    w = rand_bits(12, 1, (320, 448), 0.05)
+    out = torch.zeros(320 * 448, dtype=torch.bfloat16, device=DEV)
+    B.gllm_op_pack_weight(to_dev_bits(w), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(out).reshape(320, 448), tiled_bits(w))
+    part = torch.zeros(128 * 192, dtype=torch.bfloat16, device=DEV)
+    B.gllm_op_pack_weight(to_dev_bits(w)[64:192, :192], part)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(part).reshape(128, 192), tiled_bits(np.ascontiguousarray(w[64:192, :192])))
+    for bad in (to_dev_bits(w)[:100], to_dev_bits(w)[:, :100]):          # rows / columns that are no multiple of 64
+        with pytest.raises(B.GllmError) as e:
+            B.gllm_op_pack_weight(bad, out)
+        assert e.value.status == -7          # GLLM_E_UNSUPPORTED
+    M, N, K, k = 70, 256, 448, 192
+    a = rand_bits(12, 2, (M, K), 1.0)
+    wn = rand_bits(12, 3, (N, K), 0.05)
+    res = torch.zeros(M, N, dtype=torch.float32, device=DEV)
+    B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, 256)), to_dev_weight(wn), res, M, N, k, B.GEMM_STORE_F32, -1)
+    torch.cuda.synchronize()
+    ref = oracle.linear(oracle.bf16_to_f64(a)[:, :k], np.ascontiguousarray(wn[:, :k]))
+    assert np.abs(res.cpu().numpy() - ref).max() <= 2e-5 * np.abs(ref).max() + 1e-6
+    with pytest.raises(B.GllmError):          # a k extent that is no multiple of 64
+        B.gllm_op_gemm_bf16(to_dev_bits(padded_rows(a, 256)), to_dev_weight(wn), res, M, N, k, B.GEMM_STORE_F32, -1, ldw=200)
