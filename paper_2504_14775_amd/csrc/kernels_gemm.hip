@@ -27,6 +27,7 @@
 namespace {
 
 constexpr int BK = 64;
+constexpr int kAuxNonTemporal = 2;  // cache-policy operand of global_load_lds: the nt bit
 
 // silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (1 ulp each; the result is rounded to bf16)
 __device__ __forceinline__ float silu(float z) {
@@ -52,7 +53,7 @@ __device__ __forceinline__ int xcd_contiguous(int wg, int count) {
 // the activations are re-read from the caches by every tile column, so where LDS cannot hold one more stage of both
 // (256x256: two of each fill 128 of the 160 KiB) the W tile alone gets the third: its loads then have two k-steps
 // to land instead of one.
-template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS, bool W_ONCE = false>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ W,
                                           int64_t ldw, void* __restrict__ out, int64_t ldc, int M, int K,
                                           int tiles_m, int tiles_n, int n_base, int tile_idx, int split, int num_splits,
@@ -113,10 +114,13 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     auto issue_w = [&](int kt, int stage) {
         unsigned char* sbase = smem + W_BASE + stage * W_STAGE;
         const char* w_kt = w_tile + (int64_t)(kt + kt_base) * kWBlockBytes + voff_w;
+        // group g = rows 8g .. 8g+7 of the tile: row block g / 8, KiB g % 8 of that block.  With one band of rows
+        // (W_ONCE) every byte of W is read by one workgroup, once: those loads carry the non-temporal hint, which
+        // keeps the one-pass stream from displacing the A panel in L2 (5-10 % on the weight-streaming products).
 #pragma unroll
         for (int i = 0; i < GW; ++i) {
-            const int g = wave + i * NW;  // rows 8g .. 8g+7 of the tile: row block g / 8, KiB g % 8 of that block
-            __builtin_amdgcn_global_load_lds((gptr_t)(w_kt + (int64_t)(g >> 3) * w_blocks_k * kWBlockBytes + (g & 7) * 1024), (lptr_t)(sbase + g * 1024), 16, 0, 0);
+            const int g = wave + i * NW;
+            __builtin_amdgcn_global_load_lds((gptr_t)(w_kt + (int64_t)(g >> 3) * w_blocks_k * kWBlockBytes + (g & 7) * 1024), (lptr_t)(sbase + g * 1024), 16, 0, W_ONCE ? kAuxNonTemporal : 0);
         }
     };
 
@@ -286,7 +290,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS, bool W_ONCE = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                     const bf16_t* __restrict__ W, int64_t ldw,
                                                                     void* __restrict__ out, int64_t ldc, int M,
@@ -298,8 +302,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const bf16_t*
     // as the plain per-share numbering would place them, the L2 sees half as many tiles per panel).
     const int num_tiles = tiles_m * tiles_n;
     const int v = xcd_contiguous(blockIdx.x + blockIdx.y * num_tiles, num_tiles * (int)gridDim.y);
-    gemm_tile<BM, BN, WGM, WGN, MODE, NS, NSW>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, v % num_tiles, v / num_tiles,
-                                          gridDim.y, split_stride);
+    gemm_tile<BM, BN, WGM, WGN, MODE, NS, NSW, W_ONCE>(A, lda, W, ldw, out, ldc, M, K, tiles_m, tiles_n, 0, v % num_tiles,
+                                                       v / num_tiles, gridDim.y, split_stride);
 }
 
 // Two tile shapes in one launch: the first big_tiles workgroups cover columns [0, n_split) with 256x256
@@ -337,13 +341,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_rowmix_kernel(const bf16_t* __r
                                                 split_stride, bands * 256);
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
-hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
-                       int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
-    if (n % BN != 0) return hipErrorInvalidValue;
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS, int NSW, bool W_ONCE>
+hipError_t launch_tile_w(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
+                         int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
     const int tiles_m = (int)ceil_div(m, BM), tiles_n = n / BN;
     const size_t smem = (NS * BM + NSW * BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, NS, NSW>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, MODE, NS, NSW, W_ONCE>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -354,6 +357,15 @@ hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ld
     kern<<<dim3(tiles_m * tiles_n, splits), 64 * WGM * WGN, smem, stream>>>(a, lda, w, ldw, out, ldc, m, k, tiles_m,
                                                                           tiles_n, split_stride);
     return hipGetLastError();
+}
+
+// All rows in one band: the weights are read once (W_ONCE, see gemm_tile).
+template <int BM, int BN, int WGM, int WGN, int MODE, int NS = 2, int NSW = NS>
+hipError_t launch_tile(const bf16_t* a, int64_t lda, const bf16_t* w, int64_t ldw, void* out, int64_t ldc, int m,
+                       int n, int k, int splits, int64_t split_stride, hipStream_t stream) {
+    if (n % BN != 0) return hipErrorInvalidValue;
+    return m <= BM ? launch_tile_w<BM, BN, WGM, WGN, MODE, NS, NSW, true>(a, lda, w, ldw, out, ldc, m, n, k, splits, split_stride, stream)
+                   : launch_tile_w<BM, BN, WGM, WGN, MODE, NS, NSW, false>(a, lda, w, ldw, out, ldc, m, n, k, splits, split_stride, stream);
 }
 
 template <int MODE>
