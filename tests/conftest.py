@@ -11,6 +11,8 @@ if ROOT not in sys.path:
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
     config.addinivalue_line("markers", "timeout: per-test time limit (pytest-timeout; ignored when the plugin is absent)")
+    import helpers
+    helpers._capture_manager = config.pluginmanager.getplugin("capturemanager")
 
 
 @pytest.fixture(scope="session")

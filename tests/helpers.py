@@ -1,9 +1,25 @@
 """Shared test plumbing: synthetic inputs as host numpy arrays (bf16 as uint16 bits)."""
 from __future__ import annotations
 
+import sys
+
 import numpy as np
 
 from paper_2504_14775_amd import synth
+
+
+_capture_manager = None          # pytest's capture manager, set by conftest.pytest_configure
+
+
+def say(msg: str) -> None:
+    """A progress line of a long test: printed as usual (pytest shows it with a failure) and, while pytest captures
+    output, also written to the real stderr, so that whoever watches the run sees that it is alive."""
+    print(msg, flush=True)
+    cm = _capture_manager
+    if cm is not None and cm.is_globally_capturing():
+        with cm.global_and_fixture_disabled():
+            sys.stderr.write(msg + "\n")
+            sys.stderr.flush()
 
 
 def layer_weights_np(shape, seed, layers=None):

@@ -36,6 +36,7 @@ import oracle
 from paper_2504_14775_amd import binding as B
 from paper_2504_14775_amd import synth
 from gpu_util import DEV, bits_of, parity_report
+from helpers import say
 
 # the oracle's samples take minutes of CPU time at the larger shapes: these tests carry their own time limit, which
 # takes precedence over a shorter one given on the command line
@@ -201,18 +202,18 @@ def teacher_forced_layers(tag, shape, stage, host_w, batch, hidden, k_pool, v_po
                                       smp.sub.num_blocks, smp.kp, smp.vp, xs, smp.need, round_operands=True)[smp.need]
             rep["noise_mean_rel"] = float(np.abs(noisy - ref).sum() / np.abs(ref).sum())
             rep["noise_max_scaled"] = float(np.abs(noisy - ref).max()) / max(1.0, rep["rms_ref"])
-            print(f"[parity] {tag} layer {l}: LITERAL BAR MISSED (mean_rel={rep['mean_rel_bf16']:.4g} vs {TOL_MEAN_REL}, "
+            say(f"[parity] {tag} layer {l}: LITERAL BAR MISSED (mean_rel={rep['mean_rel_bf16']:.4g} vs {TOL_MEAN_REL}, "
                   f"max_scaled={rep['max_abs_f32_scaled']:.4g} vs {TOL_MAX_SCALED}); exact arithmetic on bf16 operands scores "
-                  f"mean_rel={rep['noise_mean_rel']:.4g} max_scaled={rep['noise_max_scaled']:.4g} on the same rows", flush=True)
-        print(f"[parity] {tag} layer {l}: delta_rel={rep['delta_rel']:.4g} rows={len(rows)} ({time.time() - t0:.1f} s)", flush=True)
+                  f"mean_rel={rep['noise_mean_rel']:.4g} max_scaled={rep['noise_max_scaled']:.4g} on the same rows")
+        say(f"[parity] {tag} layer {l}: delta_rel={rep['delta_rel']:.4g} rows={len(rows)} ({time.time() - t0:.1f} s)")
         reports.append(rep)
     set_layers(stage, 0, L)
     worst_mean = max(r["mean_rel_bf16"] for r in reports)
     worst_max = max(r["max_abs_f32_scaled"] for r in reports)
     worst_delta = max(r["delta_rel"] for r in reports)
-    print(f"[parity] {tag}: worst layer of {L}: mean_rel={worst_mean:.4g} (bar {TOL_MEAN_REL}) max_scaled={worst_max:.4g} "
+    say(f"[parity] {tag}: worst layer of {L}: mean_rel={worst_mean:.4g} (bar {TOL_MEAN_REL}) max_scaled={worst_max:.4g} "
           f"(bar {TOL_MAX_SCALED}) "
-          f"delta_rel={worst_delta:.4g}", flush=True)
+          f"delta_rel={worst_delta:.4g}")
     for l, r in enumerate(reports):
         if not r["literal"]:
             assert r["mean_rel_bf16"] <= max(TOL_MEAN_REL, COMPOUND_MEAN * r["noise_mean_rel"]), (tag, l, r)
@@ -220,8 +221,8 @@ def teacher_forced_layers(tag, shape, stage, host_w, batch, hidden, k_pool, v_po
             assert r["mean_rel_bf16"] <= CAP_MEAN_REL and r["max_abs_f32_scaled"] <= CAP_MAX_SCALED, (tag, l, r)
         assert r["delta_rel"] <= TOL_DELTA_REL, (tag, l, r)
     missed = [l for l, r in enumerate(reports) if not r["literal"]]
-    print(f"[parity] {tag}: {L - len(missed)} of {L} layers meet the stated tolerance literally"
-          + (f"; layers {missed} are bounded by the noise of bf16 operands instead" if missed else ""), flush=True)
+    say(f"[parity] {tag}: {L - len(missed)} of {L} layers meet the stated tolerance literally"
+          + (f"; layers {missed} are bounded by the noise of bf16 operands instead" if missed else ""))
     return reports
 
 
@@ -250,7 +251,7 @@ def full_depth(tag, shape, stage, host_w, batch, hidden, k_pool, v_pool, lead, c
             assert int((after != before).sum()) > 0
             del after
         del ck_before, cv_before
-    print(f"  {tag}: properties hold on all {T} rows; running the oracle (two readings) on the sample", flush=True)
+    say(f"  {tag}: properties hold on all {T} rows; running the oracle (two readings) on the sample")
     rows = lead.rows_full
     got16, got32 = bits_of(out[rows]), out32[rows].cpu().numpy()
     xs = bits_of(hidden[rows])
@@ -259,29 +260,30 @@ def full_depth(tag, shape, stage, host_w, batch, hidden, k_pool, v_pool, lead, c
         refs[reading], _ = oracle.stage_forward(shape, host_w, lead.sub.new_tokens, lead.sub.cached_len,
                                                 lead.sub.block_tables, lead.sub.num_blocks, lead.kp.copy(), lead.vp.copy(),
                                                 xs, round_operands=(reading == "bf16_operands"))
+        say(f"  {tag}: oracle[{reading}] done")
     rep = parity_report(f"{tag} full depth vs oracle[plain]", got16, got32, refs["plain"])
     plain = refs["plain"]
     rms = max(1.0, float(np.sqrt((plain ** 2).mean())))
     yard_mean = float(np.abs(refs["bf16_operands"] - plain).sum() / np.abs(plain).sum())
     yard_max = float(np.abs(refs["bf16_operands"] - plain).max()) / rms
-    print(f"[parity] {tag} full depth: rounding noise of bf16 operands (oracle[bf16_operands] vs oracle[plain]): "
+    say(f"[parity] {tag} full depth: rounding noise of bf16 operands (oracle[bf16_operands] vs oracle[plain]): "
           f"mean_rel={yard_mean:.4g} max_scaled={yard_max:.4g}; library / noise = "
           f"{rep['mean_rel_bf16'] / yard_mean:.3f} (mean) {rep['max_abs_f32_scaled'] / yard_max:.3f} (max); "
-          f"stated bars {TOL_MEAN_REL} / {TOL_MAX_SCALED}", flush=True)
+          f"stated bars {TOL_MEAN_REL} / {TOL_MAX_SCALED}")
     assert rep["mean_rel_bf16"] <= COMPOUND_MEAN * yard_mean + 2.0 ** -10, (rep, yard_mean)
     assert rep["max_abs_f32_scaled"] <= COMPOUND_MAX * yard_max + 2.0 ** -10, (rep, yard_max)
     return rep
 
 
 def run_config(name, seed=0, lead_rows=8, n_decode=8, wide_layers=None, depth_rows=8, depth_decode=8):
-    print(f"full-size parity: {name}", flush=True)
+    say(f"full-size parity: {name}")
     t0 = time.time()
     shape = synth.SHAPES[name]
     batch = synth.make_batch(name, seed)
     stage, host_w = load_stage(shape, seed, [batch])
     k_pool, v_pool = synth.make_pool(shape, seed, batch.num_blocks, device=DEV)
-    print(f"  weights loaded, pool generated: {batch.num_blocks} pages, {2 * k_pool.numel() * 2 / 1e9:.1f} GB "
-          f"({time.time() - t0:.0f} s)", flush=True)
+    say(f"  weights loaded, pool generated: {batch.num_blocks} pages, {2 * k_pool.numel() * 2 / 1e9:.1f} GB "
+          f"({time.time() - t0:.0f} s)")
     hidden = synth.make_hidden(shape, seed, batch.num_tokens, device=DEV)
     stage.bind_kv_pool(k_pool, v_pool, batch.num_blocks)
     item_rows = 128 // max(1, min(8, shape.n_q_heads // shape.n_kv_heads))
@@ -292,10 +294,10 @@ def run_config(name, seed=0, lead_rows=8, n_decode=8, wide_layers=None, depth_ro
         wide_layers = range(shape.num_layers)
     depth = make_sample(shape, batch, k_pool, v_pool, depth_decode, ("lead", depth_rows), item_rows)   # full-depth sample
     teacher_forced_layers(name, shape, stage, host_w, batch, hidden, k_pool, v_pool, lead, wide, set(wide_layers))
-    print(f"  every layer holds on its own ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  every layer holds on its own ({time.time() - t0:.0f} s)")
     rep = full_depth(name, shape, stage, host_w, batch, hidden, k_pool, v_pool, depth)
     stage.destroy()
-    print(f"  done ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  done ({time.time() - t0:.0f} s)")
     return rep
 
 
@@ -327,17 +329,17 @@ def test_llama3_8b_one_layer_all_rows():
     stage.bind_kv_pool(k_pool, v_pool, batch.num_blocks)
     stage.forward(batch.new_tokens, batch.cached_len, batch.block_tables, hidden, out, out32)
     torch.cuda.synchronize()
-    print(f"  library done; oracle on all {batch.num_tokens} rows ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  library done; oracle on all {batch.num_tokens} rows ({time.time() - t0:.0f} s)")
     ref, _ = oracle.stage_forward(shape, host_w, batch.new_tokens, batch.cached_len, batch.block_tables,
                                   batch.num_blocks, kp, vp, bits_of(hidden))
-    print(f"  oracle done ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  oracle done ({time.time() - t0:.0f} s)")
     got16, got32 = bits_of(out), out32.cpu().numpy().astype(np.float64)
     rep = parity_report(f"{name}[layer 0, all rows] vs oracle[plain]", got16, got32, ref)
     assert rep["mean_rel_bf16"] <= TOL_MEAN_REL, rep
     assert rep["max_abs_f32_scaled"] <= TOL_MAX_SCALED, rep
     # row by row, so that a few bad rows cannot hide in the mean over 2048: every row meets twice the mean bar
     row_rel = np.abs(oracle.bf16_to_f64(got16) - ref).sum(axis=1) / np.abs(ref).sum(axis=1)
-    print(f"[parity] {name}[layer 0, all rows]: worst row mean_rel={row_rel.max():.4g} (row {int(row_rel.argmax())})", flush=True)
+    say(f"[parity] {name}[layer 0, all rows]: worst row mean_rel={row_rel.max():.4g} (row {int(row_rel.argmax())})")
     assert row_rel.max() <= 2 * TOL_MEAN_REL, (int(row_rel.argmax()), float(row_rel.max()))
     # the pools: same slots changed, values within a unit in the last place of bf16
     gk, gv = bits_of(k_pool), bits_of(v_pool)
@@ -352,14 +354,14 @@ def test_llama3_70b_stage_series_of_16_batches_back_to_back():
     synchronisation in between: every batch against the properties; then the smallest and the largest batch of the
     series each on their own: every layer teacher forced (comparison A), and the largest at full depth (B)."""
     name, seed = "llama3_70b_pp4", 0
-    print(f"full-size series: {name}", flush=True)
+    say(f"full-size series: {name}")
     t0 = time.time()
     shape = synth.SHAPES[name]
     series = synth.make_series(name, seed)
     stage, host_w = load_stage(shape, seed, series)
     nb = series[0].num_blocks
     k_pool, v_pool = synth.make_pool(shape, seed, nb, device=DEV)
-    print(f"  weights loaded, pool generated: {nb} pages, {2 * k_pool.numel() * 2 / 1e9:.1f} GB ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  weights loaded, pool generated: {nb} pages, {2 * k_pool.numel() * 2 / 1e9:.1f} GB ({time.time() - t0:.0f} s)")
     hidden = [synth.make_hidden(shape, seed + 100 + i, b.num_tokens, device=DEV) for i, b in enumerate(series)]
     ck_before = slot_checksums(shape, k_pool, nb, "k")
     outs = [torch.empty(b.num_tokens, shape.hidden, dtype=torch.bfloat16, device=DEV) for b in series]
@@ -372,8 +374,8 @@ def test_llama3_70b_stage_series_of_16_batches_back_to_back():
         ev[i + 1].record()
     torch.cuda.synchronize()
     ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(len(series))]
-    print("  per-batch ms: " + " ".join(f"{t:.1f}" for t in ms), flush=True)
-    print("  per-batch tokens: " + " ".join(str(b.num_tokens) for b in series), flush=True)
+    say("  per-batch ms: " + " ".join(f"{t:.1f}" for t in ms))
+    say("  per-batch tokens: " + " ".join(str(b.num_tokens) for b in series))
     written = np.zeros((nb, 16), dtype=bool)
     for i, b in enumerate(series):
         assert torch.isfinite(outs32[i]).all(), i
@@ -383,7 +385,7 @@ def test_llama3_70b_stage_series_of_16_batches_back_to_back():
     after = slot_checksums(shape, k_pool, nb, "k")
     assert bool(((after == ck_before) | ~untouched).all())
     del after, ck_before, outs32
-    print(f"  properties hold on all 16 batches ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  properties hold on all 16 batches ({time.time() - t0:.0f} s)")
     item_rows = 128 // 8
     sizes = [b.num_tokens for b in series]
     small, large = int(np.argmin(sizes)), int(np.argmax(sizes))
@@ -397,7 +399,7 @@ def test_llama3_70b_stage_series_of_16_batches_back_to_back():
         wide = make_sample(shape, b, k_pool, v_pool, 6, ("wide",), item_rows) if (has_chunks and which == "largest") else None
         depth = make_sample(shape, b, k_pool, v_pool, 4, ("lead", 3), item_rows) if which == "largest" else None
         teacher_forced_layers(tag, shape, stage, host_w, b, hidden[i], k_pool, v_pool, lead, wide, {0, 19})
-        print(f"  {which} batch: every layer holds on its own ({time.time() - t0:.0f} s)", flush=True)
+        say(f"  {which} batch: every layer holds on its own ({time.time() - t0:.0f} s)")
         if which == "largest":
             full_depth(tag, shape, stage, host_w, b, hidden[i], k_pool, v_pool, depth, check_pool=False)
             # and the run inside the series gave the same bits as this run on its own
@@ -406,4 +408,4 @@ def test_llama3_70b_stage_series_of_16_batches_back_to_back():
             torch.cuda.synchronize()
             assert torch.equal(again.view(torch.int16), outs[i].view(torch.int16))
     stage.destroy()
-    print(f"  done ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  done ({time.time() - t0:.0f} s)")
