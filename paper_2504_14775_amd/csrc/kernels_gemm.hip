@@ -528,6 +528,14 @@ GemmPlan gemm_plan(int m, int n, int k, int mode, int max_splits, bool row_mixed
             if (deep) cost *= 0.85;
             if (cost < best_cost) { best_cost = cost; best = GemmPlan{deep ? 6 : 0, s}; }
         }
+        if (m > 128 && m <= 256 && n % 128 == 0) {
+            // 129..256 rows: 256x128 tiles take all rows in one band, so the weights are read once (with the
+            // non-temporal hint) where the 128-row shapes read them twice; measured 0.67 of a 256x256 k-step and a
+            // fixed 3; wins where the product cannot be split along k (gate/up: 4-9 % over the 128x128 tiles)
+            const int64_t tiles = (int64_t)(n / 128) * s;
+            const double cost = (double)ceil_div(tiles, 256) * (steps * 0.67 + 3.0) + plane_cost;
+            if (cost < best_cost) { best_cost = cost; best = GemmPlan{1, s}; }
+        }
         if (skinny) {
             const int64_t tiles = (int64_t)(n / 128) * s;
             const double stream = (double)n * k * 2.0 / 5.5e12 / 1.65e-6;
