@@ -12,6 +12,11 @@ device synchronisations.  Prints ONE JSON line.  `roofline` describes the bf16 M
 layer are launches of it), measured with HIP events on the launch stream in a second pass of the
 same steps; `roofline_decode_attention` gives the HBM figure of the decode attention kernel;
 `cpu_baseline` times the CPU oracle on a bounded sample of the same batch.
+
+    python bench.py --decode-rows 64 [--config llama3_8b_pp4]
+
+runs a small decode-only micro-batch on the configuration's stage shape instead (not the headline workload): there
+every kernel is a stream of weights or KV, and the line carries `roofline_whole_stage_streams`.
 """
 from __future__ import annotations
 
@@ -82,6 +87,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-index", type=int, default=0, help="batch of the 70B-shaped series")
     ap.add_argument("--layers", type=int, default=0, help="experiment: run only this many layers of the stage")
+    ap.add_argument("--decode-rows", type=int, default=0, metavar="N",
+                    help="instead of the configuration's batch: a decode-only micro-batch of N rows (contexts uniform in "
+                         "1500..3500) on the configuration's stage shape -- the small-batch regime, bound by the weight "
+                         "and KV streams; adds a whole-stage HBM roofline to the line")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="experiment: gllm_stage_set_option(NAME, VALUE) before running")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -118,7 +127,8 @@ def main():
     if args.layers > 0:
         import dataclasses
         shape = dataclasses.replace(shape, num_layers=args.layers)
-    batch = synth.make_batch(args.config, args.seed, args.batch_index)
+    batch = (synth.make_decode_only_batch(args.decode_rows, args.seed) if args.decode_rows > 0
+             else synth.make_batch(args.config, args.seed, args.batch_index))
     T = batch.num_tokens
 
     stage = binding.stage_for_batches(shape, [batch], device=dev)
@@ -185,7 +195,7 @@ def main():
     gemm_flop_step = T * shape.gemm_flop_per_token_layer * L
     roofline = None
     extra = {}
-    traffic = measured_traffic(args.config)
+    traffic = measured_traffic(args.config if args.decode_rows == 0 else "none")
     # operands once + result once, averaged over the four projections of a layer (result: fp32 planes for QKV, O and
     # down as planned for this row count, bf16 for gate/up)
     H_, I_, NQ, QD = shape.hidden, shape.intermediate, shape.n_qkv, shape.q_dim
@@ -234,6 +244,14 @@ def main():
                 "kernel": "prefill_attention_kernel", "bound": "mfma", "achieved": round(tf, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4),
                 "avg_launch_ms": round(per_step["attn_prefill"] / L, 5), "flop_per_launch": pf}
+        if args.decode_rows > 0:
+            # few rows: every kernel of the stage is a stream -- the weights once and the batch's KV once per layer
+            stage_bytes = (shape.weight_elems_per_layer * 2 + kvb) * L
+            gbs = stage_bytes / (ms_per_step * 1e-3) / 1e9
+            extra["roofline_whole_stage_streams"] = {
+                "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_step": stage_bytes,
+                "note": "layer weights once + KV of the batch once, per layer, over the whole step time (all kernels)"}
         extra["kernel_ms_per_step"] = {k: round(v, 4) for k, v in per_step.items()}
         extra["kernel_ms_sum"] = round(sum(per_step.values()), 4)
 
@@ -280,7 +298,8 @@ def main():
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "setup_passes": SETUP_PASSES, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.config + (f"[first {args.layers} layers]" if args.layers > 0 else ""), "layers": L, "tokens_per_batch": T,
+        "config": {"workload": args.config + (f"/decode_only_{args.decode_rows}" if args.decode_rows > 0 else "")
+                               + (f"[first {args.layers} layers]" if args.layers > 0 else ""), "layers": L, "tokens_per_batch": T,
                    "prefill_tokens": int(batch.new_tokens[batch.new_tokens > 1].sum()),
                    "decode_seqs": int((batch.new_tokens == 1).sum()),
                    "mean_decode_context": float(np.mean(batch.cached_len[batch.new_tokens == 1])) if (batch.new_tokens == 1).any() else 0.0,

@@ -287,6 +287,13 @@ def make_batch(name: str, seed: int = 0, index: int = 0) -> Batch:
     raise KeyError(name)
 
 
+def make_decode_only_batch(rows: int, seed: int = 0, lo: int = 1500, hi: int = 3500) -> Batch:
+    """A small decode-only micro-batch -- what the paper's Eq. 4 leaves of the running requests per micro-batch when few
+    are decoding: `rows` sequences with one new token each over cached lengths uniform in [lo, hi]."""
+    c = uniform_ints(seed, _ST_BATCH + 300, rows, lo, hi)
+    return build_batch([(1, int(x)) for x in c], seed, spare_blocks=64, label=f"decode_only_{rows}")
+
+
 def make_series(name: str = "llama3_70b_pp4", seed: int = 0, count: int = 16,
                 pool_decodes: int = 512) -> List[Batch]:
     """16 consecutive batches over one shared pool.
